@@ -1,0 +1,174 @@
+/*
+ * CPU oracle for the SwitchBack int8 linear layer (arxiv 2304.13013, Section 2.2.1, Algorithm 1).
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It is a plain, slow, obviously-correct statement of
+ * what the layer computes, written from the paper, and it shares no code with the GPU library.  Only the
+ * tests, the smoke check and the benchmark's cpu_baseline leg may call it.
+ *
+ * All matrices are dense row-major.  bf16 values travel as their 16-bit patterns (uint16_t); widening a
+ * bf16 to binary32 is exact (the pattern becomes the high half of the float).  "fl" below means one IEEE
+ * binary32 operation, round-to-nearest-even.  The file must be compiled without fast-math and without
+ * floating-point contraction so that each "fl" is exactly one rounding.
+ *
+ * Paper notation: X [b,n] inputs, W [m,n] weights, Y [b,m] outputs, dY [b,m], dX [b,n], dW [m,n]
+ * (Section 2.2.1 "Notation").  int8 codes lie in [-127,127] (Section 2.2.1 "Quantization").
+ *
+ * Readings taken where the paper is silent (each is listed in the design notes as well):
+ *   - round() is round-half-to-even;
+ *   - the scale is formed first, t = fl(127/absmax), then each element is fl(x*t)   (literal order of
+ *     the row-wise and tensor-wise quantization equations);
+ *   - an all-zero row (or tensor), or an absmax so small that 127/absmax overflows binary32, quantizes
+ *     to all zeros and stores state 0;
+ *   - the state is the absmax itself, kept in binary32;
+ *   - dequantization order: c = fl(state_W/127^2) once, r_i = fl(state_row[i]*c) per row,
+ *     y = fl((float)acc * r_i) per element                      (the forward equation with dequantization);
+ *   - Algorithm 1's backward dequantizes with the state of the quantized dY (its listing reuses the
+ *     forward's name for it).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ---- small scalar helpers -------------------------------------------------------------------------- */
+
+static float bf16_to_f32(uint16_t h) {
+    uint32_t u = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return f;
+}
+
+/* binary32 -> bf16, round-to-nearest-even on the 16 dropped bits.  NaN is out of contract (kept quiet). */
+static uint16_t f32_to_bf16_rne(float f) {
+    uint32_t u;
+    memcpy(&u, &f, sizeof u);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
+    uint32_t lsb = (u >> 16) & 1u;
+    u += 0x7fffu + lsb;
+    return (uint16_t)(u >> 16);
+}
+
+/* The per-row / per-tensor scale: t = fl(127/s), with the zero and overflow cases mapped to (t=0, s=0). */
+static float scale_from_absmax(float s, float *stored_state) {
+    float t = 127.0f / s;
+    if (s == 0.0f || !isfinite(t)) {
+        *stored_state = 0.0f;
+        return 0.0f;
+    }
+    *stored_state = s;
+    return t;
+}
+
+static int8_t quantize_one(float x, float t) {
+    float p = x * t;        /* fl(x * t) */
+    float r = rintf(p);     /* round-half-to-even under the default rounding mode */
+    if (r > 127.0f) r = 127.0f;
+    if (r < -127.0f) r = -127.0f;
+    return (int8_t)r;
+}
+
+/* ---- quantization (row-wise and tensor-wise quantization equations) ----------------------------------- */
+
+/* Q_row and state_row: one absmax per row. x [rows,cols] bf16 -> q [rows,cols] int8, state [rows] f32. */
+void sbo_quantize_rowwise(const uint16_t *x, int64_t rows, int64_t cols, int8_t *q, float *state) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < rows; ++i) {
+        const uint16_t *xi = x + i * cols;
+        float s = 0.0f;
+        for (int64_t j = 0; j < cols; ++j) {
+            float a = fabsf(bf16_to_f32(xi[j]));
+            if (a > s) s = a;
+        }
+        float t = scale_from_absmax(s, &state[i]);
+        for (int64_t j = 0; j < cols; ++j) q[i * cols + j] = quantize_one(bf16_to_f32(xi[j]), t);
+    }
+}
+
+/* Q_tensor and state_tensor: one absmax for the whole matrix.  w [rows,cols] -> q [rows,cols],
+ * q_t [cols,rows] (the transposed copy; may be NULL), state[0].  Because the scale is a single scalar,
+ * quantizing the transpose equals transposing the quantized matrix, so q_t is just q transposed. */
+void sbo_quantize_tensorwise(const uint16_t *w, int64_t rows, int64_t cols, int8_t *q, int8_t *q_t,
+                             float *state) {
+    float s = 0.0f;
+    for (int64_t e = 0; e < rows * cols; ++e) {
+        float a = fabsf(bf16_to_f32(w[e]));
+        if (a > s) s = a;
+    }
+    float t = scale_from_absmax(s, &state[0]);
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < rows; ++i)
+        for (int64_t j = 0; j < cols; ++j) {
+            int8_t v = quantize_one(bf16_to_f32(w[i * cols + j]), t);
+            q[i * cols + j] = v;
+            if (q_t) q_t[j * rows + i] = v;
+        }
+}
+
+/* ---- integer matmul ("int8 matmul" under-brace of the forward equation) -------------------------------- */
+
+/* acc[i,j] = sum_k a[i,k] * b[j,k]; a [M,K], b [N,K] int8, acc [M,N] int32.  The sum is formed exactly in
+ * int64; returns 0 when every sum fits int32 (always so while 127^2*K < 2^31), 1 otherwise. */
+int sbo_matmul_int8(const int8_t *a, const int8_t *b, int64_t M, int64_t N, int64_t K, int32_t *acc) {
+    int overflow = 0;
+#pragma omp parallel for schedule(static) reduction(| : overflow)
+    for (int64_t i = 0; i < M; ++i)
+        for (int64_t j = 0; j < N; ++j) {
+            int64_t s64 = 0;
+            for (int64_t k = 0; k < K; ++k) s64 += (int32_t)a[i * K + k] * (int32_t)b[j * K + k];
+            if (s64 > INT32_MAX || s64 < INT32_MIN) overflow = 1;
+            acc[i * N + j] = (int32_t)s64;
+        }
+    return overflow;
+}
+
+/* ---- dequantization (forward equation with dequantization) --------------------------------------------- */
+
+/* y32[i,j] = fl((float)acc[i,j] * fl(state_row[i] * fl(state_tensor/16129)));
+ * y64[i,j] = acc * state_row[i] * state_tensor / 16129 in binary64 (may be NULL). */
+void sbo_dequantize(const int32_t *acc, int64_t M, int64_t N, const float *state_row, float state_tensor,
+                    float *y32, double *y64) {
+    float c = state_tensor / 16129.0f;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M; ++i) {
+        float r = state_row[i] * c;
+        for (int64_t j = 0; j < N; ++j) {
+            y32[i * N + j] = (float)acc[i * N + j] * r;
+            if (y64)
+                y64[i * N + j] =
+                    (double)acc[i * N + j] * (double)state_row[i] * (double)state_tensor / 16129.0;
+        }
+    }
+}
+
+void sbo_round_to_bf16(const float *y, int64_t count, uint16_t *out) {
+    for (int64_t e = 0; e < count; ++e) out[e] = f32_to_bf16_rne(y[e]);
+}
+
+/* ---- weight gradient (Algorithm 1: the 16-bit matmul of dY^T and X) ------------------------------------- */
+
+/* dw64[j,k] = sum_i dy[i,j] * x[i,k] in binary64, i ascending.  dy [b,m], x [b,n] bf16, dw64 [m,n].
+ * A bf16 x bf16 product is exact in binary64 (16 significant bits), so only the additions round. */
+void sbo_weight_grad(const uint16_t *dy, const uint16_t *x, int64_t b, int64_t n, int64_t m, double *dw64) {
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < m; ++j) {
+        double *row = dw64 + j * n;
+        for (int64_t k = 0; k < n; ++k) row[k] = 0.0;
+        for (int64_t i = 0; i < b; ++i) {
+            double g = (double)bf16_to_f32(dy[i * m + j]);
+            const uint16_t *xi = x + i * n;
+            for (int64_t k = 0; k < n; ++k) row[k] += g * (double)bf16_to_f32(xi[k]);
+        }
+    }
+}
+
+int sbo_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

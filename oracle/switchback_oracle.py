@@ -1,0 +1,152 @@
+"""ctypes front end of the plain-C SwitchBack oracle (arxiv 2304.13013, Section 2.2.1, Algorithm 1).
+
+TEST INFRASTRUCTURE ONLY: the tests, the smoke check and the benchmark's cpu_baseline leg call this; the GPU
+library never does, and nothing here imports the GPU package.  Arrays are numpy; bf16 tensors are uint16 arrays
+holding the bf16 bit patterns.  Every function allocates and returns its outputs.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "switchback_oracle.c")
+_LIB = os.path.join(_HERE, "libswitchback_oracle.so")
+
+# No fast-math, no contraction: every binary32 operation in the C file must round exactly once.
+_CFLAGS = ["-O2", "-std=c11", "-fopenmp", "-ffp-contract=off", "-fno-fast-math", "-shared", "-fPIC", "-Wall"]
+
+
+def build(force=False):
+    """Compile the oracle with gcc (skipped when the library is newer than its source unless force)."""
+    if not force and os.path.exists(_LIB) and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC):
+        return _LIB
+    subprocess.check_call(["gcc", *_CFLAGS, "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        _lib.sbo_matmul_int8.restype = ctypes.c_int
+        _lib.sbo_num_threads.restype = ctypes.c_int
+    return _lib
+
+
+def _p(a):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _i64(v):
+    return ctypes.c_int64(int(v))
+
+
+def _bf16(a):
+    a = np.ascontiguousarray(a)
+    assert a.dtype == np.uint16 and a.ndim == 2, "bf16 tensors are 2-D uint16 arrays of bit patterns"
+    return a
+
+
+def num_threads():
+    return int(_load().sbo_num_threads())
+
+
+def quantize_rowwise(x):
+    """Q_row and state_row (row-wise quantization equation): returns (q int8 [r,c], state f32 [r])."""
+    x = _bf16(x)
+    r, c = x.shape
+    q = np.empty((r, c), np.int8)
+    state = np.empty(r, np.float32)
+    _load().sbo_quantize_rowwise(_p(x), _i64(r), _i64(c), _p(q), _p(state))
+    return q, state
+
+
+def quantize_tensorwise(w):
+    """Q_tensor and state_tensor (tensor-wise quantization equation): returns (q [r,c], q_t [c,r], state f32)."""
+    w = _bf16(w)
+    r, c = w.shape
+    q = np.empty((r, c), np.int8)
+    q_t = np.empty((c, r), np.int8)
+    state = np.empty(1, np.float32)
+    _load().sbo_quantize_tensorwise(_p(w), _i64(r), _i64(c), _p(q), _p(q_t), _p(state))
+    return q, q_t, state[0]
+
+
+def matmul_int8(a, b):
+    """acc = a b^T exactly, a [M,K], b [N,K] int8 -> int32 [M,N].  Raises if a sum leaves int32."""
+    a = np.ascontiguousarray(a)
+    b = np.ascontiguousarray(b)
+    assert a.dtype == np.int8 and b.dtype == np.int8 and a.shape[1] == b.shape[1]
+    M, K = a.shape
+    N = b.shape[0]
+    acc = np.empty((M, N), np.int32)
+    if _load().sbo_matmul_int8(_p(a), _p(b), _i64(M), _i64(N), _i64(K), _p(acc)):
+        raise OverflowError("int8 matmul left the int32 range")
+    return acc
+
+
+def dequantize(acc, state_row, state_tensor, want_f64=False):
+    """Forward equation with dequantization: y32 (binary32, in the oracle's operation order) and, optionally,
+    the same product evaluated in binary64."""
+    acc = np.ascontiguousarray(acc)
+    state_row = np.ascontiguousarray(state_row, dtype=np.float32)
+    assert acc.dtype == np.int32 and state_row.shape == (acc.shape[0],)
+    M, N = acc.shape
+    y32 = np.empty((M, N), np.float32)
+    y64 = np.empty((M, N), np.float64) if want_f64 else None
+    _load().sbo_dequantize(_p(acc), _i64(M), _i64(N), _p(state_row), ctypes.c_float(float(state_tensor)),
+                           _p(y32), _p(y64) if want_f64 else None)
+    return (y32, y64) if want_f64 else y32
+
+
+def round_to_bf16(y32):
+    """binary32 -> bf16 bit patterns, round-to-nearest-even."""
+    y32 = np.ascontiguousarray(y32, dtype=np.float32)
+    out = np.empty(y32.shape, np.uint16)
+    _load().sbo_round_to_bf16(_p(y32), _i64(y32.size), _p(out))
+    return out
+
+
+def weight_grad(dy, x):
+    """dW = dY^T X accumulated in binary64 (Algorithm 1's 16-bit matmul, as its exact definition): f64 [m,n]."""
+    dy = _bf16(dy)
+    x = _bf16(x)
+    assert dy.shape[0] == x.shape[0]
+    b, m = dy.shape
+    n = x.shape[1]
+    dw = np.empty((m, n), np.float64)
+    _load().sbo_weight_grad(_p(dy), _p(x), _i64(b), _i64(n), _i64(m), _p(dw))
+    return dw
+
+
+def forward(x, w):
+    """Algorithm 1 forward.  Returns a dict with every intermediate: xq, state_x, wq, wq_t, state_w, acc,
+    y32 (binary32 before the bf16 cast) and y_bf16."""
+    xq, state_x = quantize_rowwise(x)
+    wq, wq_t, state_w = quantize_tensorwise(w)
+    acc = matmul_int8(xq, wq)
+    y32 = dequantize(acc, state_x, state_w)
+    return dict(xq=xq, state_x=state_x, wq=wq, wq_t=wq_t, state_w=state_w, acc=acc, y32=y32,
+                y_bf16=round_to_bf16(y32))
+
+
+def backward_input(dy, wq_t, state_w):
+    """Algorithm 1 input gradient: dX = dequant(Q_row(dY) Q_tensor(W)); contraction over m, so the right
+    operand is the transposed code matrix wq_t [n,m]."""
+    gq, state_g = quantize_rowwise(dy)
+    acc = matmul_int8(gq, wq_t)
+    dx32 = dequantize(acc, state_g, state_w)
+    return dict(gq=gq, state_g=state_g, acc=acc, dx32=dx32, dx_bf16=round_to_bf16(dx32))
+
+
+def backward_weight(dy, x):
+    """Algorithm 1 weight gradient: binary64 sum, its binary32 rounding and the bf16 rounding of that."""
+    dw64 = weight_grad(dy, x)
+    dw32 = dw64.astype(np.float32)
+    return dict(dw64=dw64, dw32=dw32, dw_bf16=round_to_bf16(dw32))
