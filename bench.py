@@ -1,0 +1,206 @@
+#!/usr/bin/env python3
+"""Benchmark of the SwitchBack linear layer (Algorithm 1 of arxiv 2304.13013) on one MI355X.
+
+One "step" is the whole hot path over the ViT-H/14-shaped workload: for each of the four transformer linear
+layers (qkv, proj, fc1, fc2; b = 128 x 257 tokens) a forward pass, the input gradient and the weight gradient
+through the C ABI.  The headline value counts 6*b*n*m flop per layer (the three products; quantization is
+overhead).  Beside it: the same three products as bf16 torch matmuls on the same GPU (the paper's baseline), the
+per-kernel times with the roofline of the dominant kernel, and the CPU oracle timed on a bounded sample.
+
+Prints ONE JSON line on stdout.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK = {"hbm_GBps": 8000.0, "int8_TOPs": 5000.0, "bf16_TFLOPs": 2500.0}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="vit_h14", help="workload (default: the headline ViT-H/14 shapes)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-rows", type=int, default=0, help="token rows of the oracle sample (0 = auto)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        sys.stderr.write("bench.py: this build runs on ONE GPU (no sharding, no collectives); "
+                         "--gpus %d is not supported, use --gpus 1\n" % args.gpus)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2304_13013_amd import inputs as I
+    from paper_2304_13013_amd import switchback as sb
+
+    sb.load_library()  # fails loudly if the HIP library is not built
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = I.CONFIGS[args.config]
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(0)
+
+    def draw(shape, kind, sigma):
+        z = torch.randn(shape, generator=gen, device=dev, dtype=torch.float32)
+        if kind == "student_t3":
+            chi2 = sum(torch.randn(shape, generator=gen, device=dev) ** 2 for _ in range(3))
+            z = z / torch.sqrt(chi2 / 3.0)
+        elif kind == "outlier":
+            cols = torch.randperm(shape[1], generator=gen, device=dev)[: -(-shape[1] // 1000)]
+            z[:, cols] *= 100.0
+        return (z * sigma).to(torch.bfloat16)
+
+    layers = []
+    for L in cfg.layers:
+        x = draw((L.b, L.n), *cfg.x_dist)
+        w = draw((L.m, L.n), "normal", (1.0 / L.n) ** 0.5)
+        dy = draw((L.b, L.m), *cfg.dy_dist)
+        e = lambda shape, dt=torch.bfloat16: torch.empty(shape, dtype=dt, device=dev)
+        layers.append(dict(L=L, x=x, w=w, dy=dy, bufs=sb.LayerBuffers(L.b, L.n, L.m, dev),
+                           y=e((L.b, L.m)), dx=e((L.b, L.n)), dw=e((L.m, L.n))))
+    flop_per_step = sum(6.0 * t["L"].b * t["L"].n * t["L"].m for t in layers)
+
+    def switchback_step():
+        for t in layers:
+            sb.forward(t["x"], t["w"], bufs=t["bufs"], y=t["y"])
+            sb.backward_input(t["dy"], t["bufs"], dx=t["dx"])
+            sb.backward_weight(t["dy"], t["x"], t["bufs"], dw=t["dw"])
+
+    def bf16_step():
+        for t in layers:
+            torch.matmul(t["x"], t["w"].t(), out=t["y"])
+            torch.matmul(t["dy"], t["w"], out=t["dx"])
+            torch.matmul(t["dy"].t(), t["x"], out=t["dw"])
+
+    def timed(fn, steps, warmup):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e3 / steps
+        return max(e0.elapsed_time(e1) / steps, 0.0), wall
+
+    sb_ms, sb_wall_ms = timed(switchback_step, args.steps, args.warmup)
+    bf_ms, _ = timed(bf16_step, args.steps, args.warmup)
+
+    # ---- per-kernel times: the same kernels on the same shapes, one event pair around each launch group ------
+    ops = {}  # name -> [total ms over reps, algorithmic work, unit kind]
+
+    def time_op(name, fn, work, kind, reps):
+        for _ in range(2):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        rec = ops.setdefault(name, [0.0, 0.0, kind])
+        rec[0] += e0.elapsed_time(e1) / reps
+        rec[1] += work
+
+    reps = max(5, min(args.steps, 20))
+    for t in layers:
+        L, bufs = t["L"], t["bufs"]
+        b, n, m = L.b, L.n, L.m
+        time_op("quantize_rowwise", lambda: sb.quantize_rowwise(t["x"], bufs.xq, bufs.state_x),
+                b * n * 3.0 + 4.0 * b, "bytes", reps)
+        time_op("quantize_rowwise", lambda: sb.quantize_rowwise(t["dy"], bufs.gq, bufs.state_g),
+                b * m * 3.0 + 4.0 * b, "bytes", reps)
+        time_op("quantize_tensorwise",
+                lambda: sb.quantize_tensorwise(t["w"], bufs.wq, bufs.wq_t, bufs.state_w, bufs.ws_fwd),
+                m * n * 6.0, "bytes", reps)
+        time_op("gemm_int8_dequant",
+                lambda: sb.matmul_int8_dequant(bufs.xq, bufs.state_x, bufs.wq, bufs.state_w, out=t["y"]),
+                2.0 * b * n * m, "int8", reps)
+        time_op("gemm_int8_dequant",
+                lambda: sb.matmul_int8_dequant(bufs.gq, bufs.state_g, bufs.wq_t, bufs.state_w, out=t["dx"]),
+                2.0 * b * n * m, "int8", reps)
+        time_op("gemm_bf16_weight_grad", lambda: sb.backward_weight(t["dy"], t["x"], bufs, dw=t["dw"]),
+                2.0 * b * n * m, "bf16", reps)
+
+    kernels = {}
+    for name, (ms, work, kind) in ops.items():
+        if kind == "bytes":
+            ach, peak, unit, bound = work / ms / 1e6, PEAK["hbm_GBps"], "GB/s", "hbm"
+        else:
+            ach, unit, bound = work / ms / 1e9, "TFLOP/s", "mfma"
+            peak = PEAK["int8_TOPs"] if kind == "int8" else PEAK["bf16_TFLOPs"]
+        kernels[name] = {"ms_per_step": round(ms, 4), "bound": bound, "achieved": round(ach, 1), "peak": peak,
+                         "unit": unit, "frac": round(ach / peak, 4)}
+    dominant = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
+    roofline = {"kernel": dominant, "bound": kernels[dominant]["bound"], "achieved": kernels[dominant]["achieved"],
+                "peak": kernels[dominant]["peak"], "unit": kernels[dominant]["unit"],
+                "frac": kernels[dominant]["frac"], "traffic": None}
+    op_sum = sum(k["ms_per_step"] for k in kernels.values())
+    quant_ms = kernels["quantize_rowwise"]["ms_per_step"] + kernels["quantize_tensorwise"]["ms_per_step"]
+
+    # ---- CPU oracle on a bounded sample of the same workload --------------------------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import switchback_oracle as oracle
+        L = max(cfg.layers, key=lambda l: l.n * l.m)
+        rows = args.cpu_sample_rows or max(8, int(6.0e9 / (3.0 * L.n * L.m)))
+        rows = min(rows, L.b)
+        idx = np.linspace(0, L.b - 1, rows).astype(np.int64)
+        li = cfg.layers.index(L)
+        d = I.make_layer_inputs(args.config, li, token_rows=idx)
+        t0 = time.perf_counter()
+        f = oracle.forward(d["x"], d["w"])
+        oracle.backward_input(d["dy"], f["wq_t"], f["state_w"])
+        oracle.backward_weight(d["dy"], d["x"])
+        secs = time.perf_counter() - t0
+        cpu = {"value": round(6.0 * rows * L.n * L.m / secs / 1e12, 5), "unit": "TFLOP/s",
+               "cores": oracle.num_threads(), "kind": "oracle", "seconds": round(secs, 2),
+               "sample": "%s layer %s (n=%d, m=%d): forward + dX + dW on %d of %d token rows (evenly spaced), "
+                         "W whole" % (args.config, L.name, L.n, L.m, rows, L.b)}
+
+    out = {
+        "metric": "SwitchBack linear fwd+bwd TFLOP/s + speedup vs bf16 linear, ViT-H shapes",
+        "value": round(flop_per_step / sb_ms / 1e9, 2),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(sb_ms, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int8+bf16",
+        "data": "synthetic",
+        "config": {"workload": "%s: %s; forward + input gradient + weight gradient of each layer" % (
+            args.config, ", ".join("%s %dx(%d->%d)" % (l.name, l.b, l.n, l.m) for l in cfg.layers))},
+        "speedup_vs_bf16_linear": round(bf_ms / sb_ms, 4),
+        "bf16_linear_ms_per_step": round(bf_ms, 4),
+        "bf16_linear_TFLOPs": round(flop_per_step / bf_ms / 1e9, 2),
+        "wall_ms_per_step": round(sb_wall_ms, 4),
+        "roofline": roofline,
+        "kernels": kernels,
+        "sum_of_kernel_ms": round(op_sum, 4),
+        "quantize_share_of_kernel_time": round(quant_ms / op_sum, 4),
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,121 @@
+/*
+ * libswitchback -- the SwitchBack int8 linear layer (arxiv 2304.13013, Section 2.2.1, Algorithm 1) for one
+ * AMD MI355X (gfx950), as a C ABI.
+ *
+ * Notation (Section 2.2.1 "Notation"): X [b,n] inputs, W [m,n] weights (an nn.Linear weight, out x in),
+ * Y = X W^T [b,m]; dY [b,m] the gradient of the loss w.r.t. Y, dX = dY W [b,n], dW = dY^T X [m,n];
+ * b = batch size x sequence length.
+ *
+ * Conventions shared by every entry point
+ *   - Every data pointer is a DEVICE pointer owned by the caller (the binding allocates with torch).  The
+ *     library never allocates, frees or synchronizes: a call only enqueues kernels on `stream` (a
+ *     hipStream_t passed as void*; NULL = the default stream).  Outputs are valid once the stream reaches them.
+ *   - Matrices are dense row-major without strides; callers flatten leading dimensions into b.
+ *   - bf16 tensors are passed as `const void*` to 16-bit patterns.  Pointers must be 16-byte aligned.
+ *   - Shapes: b >= 1 (0 is accepted and is a no-op), n % 64 == 0, m % 64 == 0, and the contraction length of
+ *     the int8 products (n for forward, m for the input gradient) at most 131072 so that 127^2 * K < 2^31.
+ *   - Inputs must be finite; NaN/Inf give unspecified values but never a fault.  There is no bias (Algorithm 1
+ *     passes only the weight).
+ *   - Return value: SB_OK or an error code; nothing is enqueued when an error is returned, except
+ *     SB_HIP_ERROR which reports a failed launch.  No exceptions, no abort, no output to stdout/stderr.
+ *   - Calls on different streams may run concurrently as long as their output / workspace buffers differ.
+ */
+#ifndef SWITCHBACK_H
+#define SWITCHBACK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SB_OK = 0,
+    SB_INVALID_ARG = 1,         /* null / negative / misaligned argument, unknown enum value */
+    SB_UNSUPPORTED_SHAPE = 2,   /* shape outside the contract above */
+    SB_WORKSPACE_TOO_SMALL = 3, /* ws_bytes < switchback_workspace_bytes(op, b, n, m) */
+    SB_HIP_ERROR = 4            /* hipGetLastError() reported a failed launch */
+} sb_status;
+
+/* Output element type of a product.  SB_I32_RAW dumps the int32 accumulators of an int8 product and skips the
+ * dequantization (verification only; not valid for the weight gradient). */
+typedef enum { SB_BF16 = 0, SB_F32 = 1, SB_I32_RAW = 2 } sb_dtype;
+
+/* Which operation a workspace is sized for. */
+typedef enum {
+    SB_OP_QUANTIZE_TENSORWISE = 0,
+    SB_OP_FORWARD = 1,
+    SB_OP_BACKWARD_INPUT = 2,
+    SB_OP_BACKWARD_WEIGHT = 3
+} sb_op;
+
+/* What the forward pass leaves for the backward pass (Algorithm 1 saves X and W in 16 bit and re-quantizes W in
+ * backward; the scale of the tensor-wise quantizer is a single scalar, so Q(W^T) = Q(W)^T and this library
+ * quantizes W once and keeps both layouts).  All five buffers are caller-provided and FILLED by
+ * switchback_forward; switchback_backward_input reads wq_t and state_w. */
+typedef struct sb_saved {
+    int8_t *xq;      /* [b,n]  Q_row(X)                                   */
+    float *state_x;  /* [b]    state_row(X): the row-wise absmax values    */
+    int8_t *wq;      /* [m,n]  Q_tensor(W)                                */
+    int8_t *wq_t;    /* [n,m]  Q_tensor(W)^T                              */
+    float *state_w;  /* [1]    state_tensor(W): the absmax of W            */
+} sb_saved;
+
+/* Row-wise quantization Q_row with its state (first quantization equation of Section 2.2.1):
+ *   state[i] = max_j |x[i,j]|,  q[i,j] = round(127/state[i] * x[i,j]),  codes in [-127,127].
+ * Arithmetic: binary32; scale t = 127/state formed first (one correctly rounded divide per row), each element is
+ * round-half-to-even of the rounded product x*t.  A row whose absmax is 0, or so small that 127/absmax
+ * overflows binary32, gets all-zero codes and state 0.
+ *   x [rows,cols] bf16 in; q [rows,cols] int8 out; state [rows] f32 out.  cols % 8 == 0, cols <= 65536. */
+int switchback_quantize_rowwise(const void *x_bf16, int64_t rows, int64_t cols, int8_t *q, float *state,
+                                void *stream);
+
+/* Tensor-wise quantization Q_tensor with its state (second quantization equation of Section 2.2.1): as above
+ * with one absmax for the whole matrix.  Also emits the transposed code matrix (the paper's fused
+ * "tensor-wise quantize transpose"), reading W from HBM once for the absmax and once for both code layouts.
+ *   w [rows,cols] bf16 in; q [rows,cols] int8 out; q_t [cols,rows] int8 out or NULL; state [1] f32 out;
+ *   ws: SB_OP_QUANTIZE_TENSORWISE workspace (partial maxima; contents are scratch).
+ *   rows % 16 == 0, cols % 16 == 0. */
+int switchback_quantize_tensorwise(const void *w_bf16, int64_t rows, int64_t cols, int8_t *q, int8_t *q_t,
+                                   float *state, void *ws, size_t ws_bytes, void *stream);
+
+/* The int8 product with fused dequantization (the dequantized forward equation of Section 2.2.1):
+ *   acc[i,j] = sum_k aq[i,k] * bq[j,k]                       (int8 x int8 -> int32, exact)
+ *   out[i,j] = (state_tensor/127^2 * state_row[i]) * acc[i,j]
+ * evaluated in binary32 as c = state_tensor/16129, r_i = state_row[i]*c, out = (float)acc * r_i, then rounded
+ * to nearest-even when out_dtype is SB_BF16.  Both operands have the contraction index contiguous.
+ *   aq [M,K] int8; state_row [M] f32; bq [N,K] int8; state_tensor [1] f32 (device); out [M,N].
+ *   K % 64 == 0, N % 64 == 0, K <= 131072.  With SB_I32_RAW the states are ignored (may be NULL). */
+int switchback_matmul_int8_dequant(const int8_t *aq, const float *state_row, const int8_t *bq,
+                                   const float *state_tensor, int64_t M, int64_t N, int64_t K, void *out,
+                                   sb_dtype out_dtype, void *stream);
+
+/* Forward pass of Algorithm 1: Y = dequant(Q_row(X) Q_tensor(W)^T).  Fills `saved` (see sb_saved).
+ *   x [b,n] bf16, w [m,n] bf16 in; y [b,m] out in y_dtype; ws: SB_OP_FORWARD workspace. */
+int switchback_forward(const void *x_bf16, const void *w_bf16, int64_t b, int64_t n, int64_t m, void *y,
+                       sb_dtype y_dtype, const sb_saved *saved, void *ws, size_t ws_bytes, void *stream);
+
+/* Input gradient of Algorithm 1: dX = dequant(Q_row(dY) Q_tensor(W)), dequantized with the state of the
+ * quantized dY and the state of W.  Reads saved->wq_t and saved->state_w; fills gq and state_g.
+ *   dy [b,m] bf16 in; dx [b,n] out in dx_dtype; gq [b,m] int8 out; state_g [b] f32 out. */
+int switchback_backward_input(const void *dy_bf16, const sb_saved *saved, int64_t b, int64_t n, int64_t m,
+                              void *dx, sb_dtype dx_dtype, int8_t *gq, float *state_g, void *stream);
+
+/* Weight gradient of Algorithm 1, the product the layer "switches back" to 16 bit for: dW = dY^T X with bf16
+ * operands and binary32 accumulation (summation order unspecified but deterministic for a given shape).
+ *   dy [b,m] bf16, x [b,n] bf16 in; dw [m,n] out, SB_BF16 or SB_F32; ws: SB_OP_BACKWARD_WEIGHT workspace. */
+int switchback_backward_weight(const void *dy_bf16, const void *x_bf16, int64_t b, int64_t n, int64_t m,
+                               void *dw, sb_dtype dw_dtype, void *ws, size_t ws_bytes, void *stream);
+
+/* Bytes of device workspace `op` needs for a layer of this shape (0 if none).  Shape arguments an op does not
+ * use are ignored (for SB_OP_QUANTIZE_TENSORWISE pass rows as m and cols as n). */
+size_t switchback_workspace_bytes(int op, int64_t b, int64_t n, int64_t m);
+
+/* Static description of a status code. */
+const char *switchback_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SWITCHBACK_H */

@@ -1,0 +1,280 @@
+// Fused absmax + int8 quantization kernels for gfx950 (row-wise and tensor-wise quantization equations of
+// Section 2.2.1 of arxiv 2304.13013).
+//
+// Arithmetic (bit-exact contract): the absmax is taken on the bf16 bit patterns (|x| is monotone in the low 15
+// bits), the scale is t = 127/absmax as one correctly rounded binary32 divide, each code is the
+// round-half-to-even integer of the rounded binary32 product x*t.  The rounding uses the 1.5*2^23 trick: adding
+// that constant to a value of magnitude <= 127.5 leaves the nearest-even integer in the low mantissa bits, whose
+// low byte is the two's-complement int8 code.  The product and the addition are separate roundings (the file is
+// compiled with contraction off), and binary32 subnormals are preserved (the default float mode of HIP kernels).
+//
+// All three kernels are HBM-bound: one 16-byte load per 8 elements, the row (or tile) stays in registers between
+// the absmax and the quantization, codes leave as 8- or 16-byte stores.
+#include "sb_common.h"
+
+namespace sb {
+namespace {
+
+constexpr float kRoundMagic = 12582912.0f;  // 1.5 * 2^23
+
+__device__ __forceinline__ unsigned int pk_absmax_u16(unsigned int running, unsigned int two_bf16) {
+    v2us a = __builtin_bit_cast(v2us, running);
+    v2us b = __builtin_bit_cast(v2us, two_bf16 & 0x7fff7fffu);
+    return __builtin_bit_cast(unsigned int, __builtin_elementwise_max(a, b));
+}
+
+__device__ __forceinline__ unsigned int absmax_of_chunk(unsigned int running, v4u c) {
+    running = pk_absmax_u16(running, c.x);
+    running = pk_absmax_u16(running, c.y);
+    running = pk_absmax_u16(running, c.z);
+    return pk_absmax_u16(running, c.w);
+}
+
+__device__ __forceinline__ unsigned int wave_max_u32(unsigned int v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        unsigned int o = (unsigned int)__shfl_xor((int)v, off, 64);
+        v = o > v ? o : v;
+    }
+    return v;
+}
+
+// absmax bit pattern (15 bits) -> (scale t, stored state).  Zero rows and rows whose scale would overflow
+// binary32 quantize to zeros and store state 0.
+__device__ __forceinline__ float scale_from_absmax_bits(unsigned int bits15, float *stored_state) {
+    float s = bf16_bits_to_float(bits15);
+    float t = 127.0f / s;
+    if (bits15 == 0u || __builtin_isinf(t)) {
+        t = 0.0f;
+        s = 0.0f;
+    }
+    *stored_state = s;
+    return t;
+}
+
+__device__ __forceinline__ unsigned int code_bits(float x, float t) {
+    float p = x * t;            // one rounding
+    float r = p + kRoundMagic;  // second rounding: nearest-even integer lands in the low mantissa bits
+    return __float_as_uint(r);
+}
+
+// 8 bf16 (4 dwords, element 2d in the low half of dword d) -> 8 int8 codes (2 dwords).
+__device__ __forceinline__ v2u quantize_chunk(v4u c, float t) {
+    unsigned int r[8];
+    r[0] = code_bits(__uint_as_float(c.x << 16), t);
+    r[1] = code_bits(__uint_as_float(c.x & 0xffff0000u), t);
+    r[2] = code_bits(__uint_as_float(c.y << 16), t);
+    r[3] = code_bits(__uint_as_float(c.y & 0xffff0000u), t);
+    r[4] = code_bits(__uint_as_float(c.z << 16), t);
+    r[5] = code_bits(__uint_as_float(c.z & 0xffff0000u), t);
+    r[6] = code_bits(__uint_as_float(c.w << 16), t);
+    r[7] = code_bits(__uint_as_float(c.w & 0xffff0000u), t);
+    // v_perm_b32: selector bytes 0-3 pick from the second operand, 4-7 from the first, 0x0c gives zero.
+    unsigned int p01 = __builtin_amdgcn_perm(r[1], r[0], 0x0c0c0400u);
+    unsigned int p23 = __builtin_amdgcn_perm(r[3], r[2], 0x0c0c0400u);
+    unsigned int p45 = __builtin_amdgcn_perm(r[5], r[4], 0x0c0c0400u);
+    unsigned int p67 = __builtin_amdgcn_perm(r[7], r[6], 0x0c0c0400u);
+    v2u out;
+    out.x = __builtin_amdgcn_perm(p23, p01, 0x05040100u);
+    out.y = __builtin_amdgcn_perm(p67, p45, 0x05040100u);
+    return out;
+}
+
+// ---- row-wise: one wavefront per row (cols <= 64*8*NCH) ---------------------------------------------------
+template <int NCH>
+__global__ __launch_bounds__(256) void quantize_rowwise_wave_kernel(const v4u *__restrict__ x, int64_t rows,
+                                                                    int chunks, v2u *__restrict__ q,
+                                                                    float *__restrict__ state) {
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;  // whole wavefront leaves; the kernel has no block-level barrier
+    const v4u *xr = x + row * chunks;
+    v4u v[NCH];
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        int c = lane + 64 * i;
+        v[i] = c < chunks ? __builtin_nontemporal_load(xr + c) : v4u{0u, 0u, 0u, 0u};
+    }
+    unsigned int m = 0;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) m = absmax_of_chunk(m, v[i]);
+    m = wave_max_u32(max(m & 0xffffu, m >> 16));
+    float s;
+    const float t = scale_from_absmax_bits(m, &s);
+    if (lane == 0) state[row] = s;
+    v2u *qr = q + row * chunks;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        int c = lane + 64 * i;
+        if (c < chunks) qr[c] = quantize_chunk(v[i], t);
+    }
+}
+
+// ---- row-wise: one 256-thread block per row (cols <= 256*8*NCH) ---------------------------------------------
+template <int NCH>
+__global__ __launch_bounds__(256) void quantize_rowwise_block_kernel(const v4u *__restrict__ x, int chunks,
+                                                                     v2u *__restrict__ q,
+                                                                     float *__restrict__ state) {
+    __shared__ unsigned int wave_max[4];
+    const int64_t row = blockIdx.x;
+    const v4u *xr = x + row * chunks;
+    v4u v[NCH];
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        int c = threadIdx.x + 256 * i;
+        v[i] = c < chunks ? __builtin_nontemporal_load(xr + c) : v4u{0u, 0u, 0u, 0u};
+    }
+    unsigned int m = 0;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) m = absmax_of_chunk(m, v[i]);
+    m = wave_max_u32(max(m & 0xffffu, m >> 16));
+    if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = m;
+    __syncthreads();
+    m = max(max(wave_max[0], wave_max[1]), max(wave_max[2], wave_max[3]));
+    float s;
+    const float t = scale_from_absmax_bits(m, &s);
+    if (threadIdx.x == 0) state[row] = s;
+    v2u *qr = q + row * chunks;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        int c = threadIdx.x + 256 * i;
+        if (c < chunks) qr[c] = quantize_chunk(v[i], t);
+    }
+}
+
+// ---- row-wise: very wide rows, two passes over the row (the second one hits L2) ---------------------------
+__global__ __launch_bounds__(256) void quantize_rowwise_wide_kernel(const v4u *__restrict__ x, int chunks,
+                                                                    v2u *__restrict__ q,
+                                                                    float *__restrict__ state) {
+    __shared__ unsigned int wave_max[4];
+    const int64_t row = blockIdx.x;
+    const v4u *xr = x + row * chunks;
+    unsigned int m = 0;
+    for (int c = threadIdx.x; c < chunks; c += 256) m = absmax_of_chunk(m, xr[c]);
+    m = wave_max_u32(max(m & 0xffffu, m >> 16));
+    if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = m;
+    __syncthreads();
+    m = max(max(wave_max[0], wave_max[1]), max(wave_max[2], wave_max[3]));
+    float s;
+    const float t = scale_from_absmax_bits(m, &s);
+    if (threadIdx.x == 0) state[row] = s;
+    v2u *qr = q + row * chunks;
+    for (int c = threadIdx.x; c < chunks; c += 256) qr[c] = quantize_chunk(xr[c], t);
+}
+
+// ---- tensor-wise pass 1: per-block partial absmax (bit patterns) --------------------------------------------
+__global__ __launch_bounds__(256) void absmax_partial_kernel(const v4u *__restrict__ w, int64_t nchunks,
+                                                             unsigned int *__restrict__ partials) {
+    __shared__ unsigned int wave_max[4];
+    unsigned int m = 0;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x; c < nchunks; c += stride)
+        m = absmax_of_chunk(m, w[c]);
+    m = wave_max_u32(max(m & 0xffffu, m >> 16));
+    if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0)
+        partials[blockIdx.x] = max(max(wave_max[0], wave_max[1]), max(wave_max[2], wave_max[3]));
+}
+
+// ---- tensor-wise pass 2: finish the absmax, quantize a 128x128 tile, emit it row-major and transposed ------
+// The transposed copy goes through LDS so that both code matrices leave in 128-byte row segments while W is read
+// once in this pass.
+constexpr int kTile = 128;
+constexpr int kTileStride = kTile + 16;  // bytes per LDS row (keeps 16-byte alignment, staggers banks)
+
+__global__ __launch_bounds__(256) void quantize_tensorwise_kernel(const v4u *__restrict__ w, int rows, int cols,
+                                                                  int8_t *__restrict__ q,
+                                                                  int8_t *__restrict__ q_t,
+                                                                  float *__restrict__ state,
+                                                                  const unsigned int *__restrict__ partials,
+                                                                  int npartials) {
+    __shared__ unsigned int wave_max[4];
+    __shared__ __attribute__((aligned(16))) unsigned char tile_t[kTile * kTileStride];
+    unsigned int m = 0;
+    for (int i = threadIdx.x; i < npartials; i += 256) m = max(m, partials[i]);
+    m = wave_max_u32(m);
+    if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = m;
+    __syncthreads();
+    m = max(max(wave_max[0], wave_max[1]), max(wave_max[2], wave_max[3]));
+    float s;
+    const float t = scale_from_absmax_bits(m, &s);
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) state[0] = s;
+
+    const int r0 = blockIdx.y * kTile, c0 = blockIdx.x * kTile;
+    const int chunks_per_row = cols >> 3;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int id = threadIdx.x + 256 * i;
+        const int lr = id >> 4, lc = (id & 15) << 3;  // local row, local first column of the 8-element chunk
+        const int r = r0 + lr, c = c0 + lc;
+        if (r < rows && c < cols) {
+            const v2u codes = quantize_chunk(w[(int64_t)r * chunks_per_row + (c >> 3)], t);
+            *reinterpret_cast<v2u *>(q + (int64_t)r * cols + c) = codes;
+            if (q_t) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    tile_t[(lc + j) * kTileStride + lr] = (unsigned char)(codes.x >> (8 * j));
+                    tile_t[(lc + 4 + j) * kTileStride + lr] = (unsigned char)(codes.y >> (8 * j));
+                }
+            }
+        }
+    }
+    if (!q_t) return;  // uniform across the grid
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int id = threadIdx.x + 256 * i;
+        const int lc = id >> 3, lr = (id & 7) << 4;  // one 16-byte piece of a transposed row
+        const int c = c0 + lc, r = r0 + lr;
+        if (c < cols && r < rows)
+            *reinterpret_cast<v4u *>(q_t + (int64_t)c * rows + r) =
+                *reinterpret_cast<const v4u *>(tile_t + lc * kTileStride + lr);
+    }
+}
+
+}  // namespace
+
+hipError_t launch_quantize_rowwise(const void *x, int64_t rows, int64_t cols, int8_t *q, float *state,
+                                   hipStream_t stream) {
+    if (rows == 0) return hipSuccess;
+    const int chunks = (int)(cols / 8);
+    const v4u *xp = static_cast<const v4u *>(x);
+    v2u *qp = reinterpret_cast<v2u *>(q);
+    const unsigned int wave_grid = (unsigned int)((rows + 3) / 4), block_grid = (unsigned int)rows;
+#define SB_WAVE(N)                                                                                          \
+    quantize_rowwise_wave_kernel<N><<<wave_grid, 256, 0, stream>>>(xp, rows, chunks, qp, state)
+#define SB_BLOCK(N) quantize_rowwise_block_kernel<N><<<block_grid, 256, 0, stream>>>(xp, chunks, qp, state)
+    if (chunks <= 64) SB_WAVE(1);
+    else if (chunks <= 128) SB_WAVE(2);
+    else if (chunks <= 192) SB_WAVE(3);
+    else if (chunks <= 256) SB_WAVE(4);
+    else if (chunks <= 512) SB_BLOCK(2);
+    else if (chunks <= 768) SB_BLOCK(3);
+    else if (chunks <= 1024) SB_BLOCK(4);
+    else if (chunks <= 1536) SB_BLOCK(6);
+    else if (chunks <= 2048) SB_BLOCK(8);
+    else quantize_rowwise_wide_kernel<<<block_grid, 256, 0, stream>>>(xp, chunks, qp, state);
+#undef SB_WAVE
+#undef SB_BLOCK
+    return hipGetLastError();
+}
+
+hipError_t launch_quantize_tensorwise(const void *w, int64_t rows, int64_t cols, int8_t *q, int8_t *q_t,
+                                      float *state, unsigned int *partials, hipStream_t stream) {
+    const int64_t nchunks = rows * cols / 8;
+    const v4u *wp = static_cast<const v4u *>(w);
+    int nblocks = (int)((nchunks + 256 * 4 - 1) / (256 * 4));
+    if (nblocks > kTensorwisePartials) nblocks = kTensorwisePartials;
+    if (nblocks < 1) nblocks = 1;
+    absmax_partial_kernel<<<nblocks, 256, 0, stream>>>(wp, nchunks, partials);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (rows == 0 || cols == 0) return hipSuccess;
+    dim3 grid((unsigned int)((cols + kTile - 1) / kTile), (unsigned int)((rows + kTile - 1) / kTile));
+    quantize_tensorwise_kernel<<<grid, 256, 0, stream>>>(wp, (int)rows, (int)cols, q, q_t, state, partials,
+                                                         nblocks);
+    return hipGetLastError();
+}
+
+}  // namespace sb

@@ -1,0 +1,44 @@
+// Shared declarations of the SwitchBack HIP library (internal; the public C ABI is include/switchback.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/switchback.h"
+
+namespace sb {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef unsigned int v2u __attribute__((ext_vector_type(2)));
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+typedef __bf16 v4bf __attribute__((ext_vector_type(4)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef unsigned short v2us __attribute__((ext_vector_type(2)));
+
+// s_waitcnt that waits only on the vector-memory counter (gfx9 encoding: vmcnt = simm16[15:14]:[3:0],
+// expcnt [6:4] and lgkmcnt [11:8] left at their maxima).
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
+__device__ __forceinline__ float bf16_bits_to_float(unsigned int bits16) { return __uint_as_float(bits16 << 16); }
+
+// Launchers (each validates nothing: the C-ABI layer has already checked shapes and pointers).
+hipError_t launch_quantize_rowwise(const void *x, int64_t rows, int64_t cols, int8_t *q, float *state,
+                                   hipStream_t stream);
+hipError_t launch_quantize_tensorwise(const void *w, int64_t rows, int64_t cols, int8_t *q, int8_t *q_t,
+                                      float *state, unsigned int *partials, hipStream_t stream);
+hipError_t launch_gemm_i8_dequant(const int8_t *aq, const float *state_row, const int8_t *bq,
+                                  const float *state_tensor, int64_t M, int64_t N, int64_t K, void *out,
+                                  sb_dtype out_dtype, hipStream_t stream);
+size_t gemm_bf16_tn_workspace_bytes(int64_t b, int64_t n, int64_t m);
+hipError_t launch_gemm_bf16_tn(const void *dy, const void *x, int64_t b, int64_t n, int64_t m, void *dw,
+                               sb_dtype dw_dtype, void *ws, hipStream_t stream);
+
+constexpr int kTensorwisePartials = 1024;  // upper bound on blocks of the tensor-wise absmax pass
+
+}  // namespace sb

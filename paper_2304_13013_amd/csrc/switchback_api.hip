@@ -1,0 +1,139 @@
+// C ABI of libswitchback: argument validation and the kernel sequence of each pass of Algorithm 1
+// (arxiv 2304.13013).  Every step runs in the HIP kernels of this library; nothing here touches tensor data.
+#include "sb_common.h"
+
+namespace {
+
+constexpr int64_t kMaxIntK = 131072;  // 127^2 * K < 2^31 needs K <= 133143; rounded down to a power of two
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+bool ok_ptr(const void *p) { return p != nullptr && aligned16(p); }
+bool ok_dtype(int d) { return d == SB_BF16 || d == SB_F32 || d == SB_I32_RAW; }
+
+int layer_shape_status(int64_t b, int64_t n, int64_t m) {
+    if (b < 0 || n <= 0 || m <= 0) return SB_INVALID_ARG;
+    if (n % 64 || m % 64 || b > (int64_t)1 << 30 || n > kMaxIntK || m > kMaxIntK) return SB_UNSUPPORTED_SHAPE;
+    if (b * n >= (int64_t)1 << 40 || b * m >= (int64_t)1 << 40) return SB_UNSUPPORTED_SHAPE;
+    return SB_OK;
+}
+
+int from_hip(hipError_t e) { return e == hipSuccess ? SB_OK : SB_HIP_ERROR; }
+
+}  // namespace
+
+extern "C" {
+
+int switchback_quantize_rowwise(const void *x_bf16, int64_t rows, int64_t cols, int8_t *q, float *state,
+                                void *stream) {
+    if (rows < 0 || cols <= 0) return SB_INVALID_ARG;
+    if (cols % 8 || cols > 65536 || rows > (int64_t)1 << 30) return SB_UNSUPPORTED_SHAPE;
+    if (rows == 0) return SB_OK;
+    if (!ok_ptr(x_bf16) || !ok_ptr(q) || state == nullptr) return SB_INVALID_ARG;
+    return from_hip(sb::launch_quantize_rowwise(x_bf16, rows, cols, q, state, static_cast<hipStream_t>(stream)));
+}
+
+int switchback_quantize_tensorwise(const void *w_bf16, int64_t rows, int64_t cols, int8_t *q, int8_t *q_t,
+                                   float *state, void *ws, size_t ws_bytes, void *stream) {
+    if (rows <= 0 || cols <= 0) return SB_INVALID_ARG;
+    if (rows % 16 || cols % 16 || rows > (int64_t)1 << 24 || cols > (int64_t)1 << 24) return SB_UNSUPPORTED_SHAPE;
+    if (!ok_ptr(w_bf16) || !ok_ptr(q) || (q_t != nullptr && !aligned16(q_t)) || state == nullptr)
+        return SB_INVALID_ARG;
+    if (ws == nullptr || !aligned16(ws)) return SB_INVALID_ARG;
+    if (ws_bytes < switchback_workspace_bytes(SB_OP_QUANTIZE_TENSORWISE, 0, cols, rows))
+        return SB_WORKSPACE_TOO_SMALL;
+    return from_hip(sb::launch_quantize_tensorwise(w_bf16, rows, cols, q, q_t, state,
+                                                   static_cast<unsigned int *>(ws),
+                                                   static_cast<hipStream_t>(stream)));
+}
+
+int switchback_matmul_int8_dequant(const int8_t *aq, const float *state_row, const int8_t *bq,
+                                   const float *state_tensor, int64_t M, int64_t N, int64_t K, void *out,
+                                   sb_dtype out_dtype, void *stream) {
+    if (M < 0 || N <= 0 || K <= 0 || !ok_dtype(out_dtype)) return SB_INVALID_ARG;
+    if (K % 64 || N % 64 || K > kMaxIntK || N > kMaxIntK || M > (int64_t)1 << 30) return SB_UNSUPPORTED_SHAPE;
+    if (M == 0) return SB_OK;
+    if (!ok_ptr(aq) || !ok_ptr(bq) || !ok_ptr(out)) return SB_INVALID_ARG;
+    if (out_dtype != SB_I32_RAW && (state_row == nullptr || state_tensor == nullptr)) return SB_INVALID_ARG;
+    return from_hip(sb::launch_gemm_i8_dequant(aq, state_row, bq, state_tensor, M, N, K, out, out_dtype,
+                                               static_cast<hipStream_t>(stream)));
+}
+
+int switchback_forward(const void *x_bf16, const void *w_bf16, int64_t b, int64_t n, int64_t m, void *y,
+                       sb_dtype y_dtype, const sb_saved *saved, void *ws, size_t ws_bytes, void *stream) {
+    int st = layer_shape_status(b, n, m);
+    if (st != SB_OK) return st;
+    if (!ok_dtype(y_dtype) || saved == nullptr) return SB_INVALID_ARG;
+    if (!ok_ptr(w_bf16) || !ok_ptr(saved->wq) || !ok_ptr(saved->wq_t) || saved->state_w == nullptr)
+        return SB_INVALID_ARG;
+    if (b > 0 && (!ok_ptr(x_bf16) || !ok_ptr(y) || !ok_ptr(saved->xq) || saved->state_x == nullptr))
+        return SB_INVALID_ARG;
+    if (ws == nullptr || !aligned16(ws)) return SB_INVALID_ARG;
+    if (ws_bytes < switchback_workspace_bytes(SB_OP_FORWARD, b, n, m)) return SB_WORKSPACE_TOO_SMALL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // Algorithm 1, forward: X_int8, state_X = row-wise quantize(X); W_int8, state_W = tensor-wise quantize(W);
+    // Y = int8 matmul fused with the dequantization.
+    hipError_t e = sb::launch_quantize_tensorwise(w_bf16, m, n, saved->wq, saved->wq_t, saved->state_w,
+                                                  static_cast<unsigned int *>(ws), s);
+    if (e != hipSuccess) return SB_HIP_ERROR;
+    if (b == 0) return SB_OK;
+    e = sb::launch_quantize_rowwise(x_bf16, b, n, saved->xq, saved->state_x, s);
+    if (e != hipSuccess) return SB_HIP_ERROR;
+    return from_hip(sb::launch_gemm_i8_dequant(saved->xq, saved->state_x, saved->wq, saved->state_w, b, m, n, y,
+                                               y_dtype, s));
+}
+
+int switchback_backward_input(const void *dy_bf16, const sb_saved *saved, int64_t b, int64_t n, int64_t m,
+                              void *dx, sb_dtype dx_dtype, int8_t *gq, float *state_g, void *stream) {
+    int st = layer_shape_status(b, n, m);
+    if (st != SB_OK) return st;
+    if (!ok_dtype(dx_dtype) || saved == nullptr) return SB_INVALID_ARG;
+    if (b == 0) return SB_OK;
+    if (!ok_ptr(dy_bf16) || !ok_ptr(dx) || !ok_ptr(gq) || state_g == nullptr || !ok_ptr(saved->wq_t) ||
+        saved->state_w == nullptr)
+        return SB_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // Algorithm 1, backward: G_int8, state_G = row-wise quantize(dY); the tensor-wise quantized, transposed W
+    // was kept by the forward pass; dX = int8 matmul over m fused with the dequantization.
+    hipError_t e = sb::launch_quantize_rowwise(dy_bf16, b, m, gq, state_g, s);
+    if (e != hipSuccess) return SB_HIP_ERROR;
+    return from_hip(sb::launch_gemm_i8_dequant(gq, state_g, saved->wq_t, saved->state_w, b, n, m, dx, dx_dtype, s));
+}
+
+int switchback_backward_weight(const void *dy_bf16, const void *x_bf16, int64_t b, int64_t n, int64_t m,
+                               void *dw, sb_dtype dw_dtype, void *ws, size_t ws_bytes, void *stream) {
+    int st = layer_shape_status(b, n, m);
+    if (st != SB_OK) return st;
+    if (dw_dtype != SB_BF16 && dw_dtype != SB_F32) return SB_INVALID_ARG;
+    if (!ok_ptr(dw) || (b > 0 && (!ok_ptr(dy_bf16) || !ok_ptr(x_bf16)))) return SB_INVALID_ARG;
+    const size_t need = switchback_workspace_bytes(SB_OP_BACKWARD_WEIGHT, b, n, m);
+    if (need > 0 && (ws == nullptr || !aligned16(ws))) return SB_INVALID_ARG;
+    if (ws_bytes < need) return SB_WORKSPACE_TOO_SMALL;
+    // Algorithm 1, backward: W_gradient = 16-bit matmul of dY^T and X (b == 0 gives an all-zero gradient).
+    return from_hip(sb::launch_gemm_bf16_tn(dy_bf16, x_bf16, b, n, m, dw, dw_dtype, ws,
+                                            static_cast<hipStream_t>(stream)));
+}
+
+size_t switchback_workspace_bytes(int op, int64_t b, int64_t n, int64_t m) {
+    switch (op) {
+        case SB_OP_QUANTIZE_TENSORWISE:
+        case SB_OP_FORWARD: return sb::kTensorwisePartials * sizeof(unsigned int);
+        case SB_OP_BACKWARD_INPUT: return 0;
+        case SB_OP_BACKWARD_WEIGHT:
+            if (b < 0 || n <= 0 || m <= 0) return 0;
+            return sb::gemm_bf16_tn_workspace_bytes(b, n, m);
+        default: return 0;
+    }
+}
+
+const char *switchback_status_string(int status) {
+    switch (status) {
+        case SB_OK: return "ok";
+        case SB_INVALID_ARG: return "invalid argument (null, negative, misaligned or unknown enum)";
+        case SB_UNSUPPORTED_SHAPE: return "unsupported shape";
+        case SB_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case SB_HIP_ERROR: return "HIP launch error";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

@@ -12,6 +12,7 @@ without generating the rest.
 The layer shapes stand in for the paper's CLIP ViT-B/16, L/14 and H/14 training workloads (Section 2.2.2; the
 inner dimensions quoted in Appendix C): b = images x tokens per image, n -> m the linear layer's widths.
 """
+import os
 from collections import namedtuple
 from concurrent.futures import ThreadPoolExecutor
 
@@ -93,7 +94,7 @@ def _fill(fn, total, out_flat):
         for s in spans:
             work(s)
     else:
-        with ThreadPoolExecutor(max_workers=8) as ex:
+        with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as ex:
             list(ex.map(work, spans))
 
 
@@ -118,14 +119,15 @@ def normal_bf16(nrows, ncols, sigma, seed, stream, rows=None):
 
 
 def student_t3_bf16(nrows, ncols, sigma, seed, stream, rows=None):
-    """sigma * Student-t(nu=3): a normal over sqrt(chi^2_3 / 3), the chi^2 from three more normal streams."""
+    """sigma * Student-t(nu=3): a normal over sqrt(chi^2_3 / 3); the chi^2_3 is the sum of a chi^2_2 variate
+    (-2 ln u, from one more uniform stream) and one squared normal."""
     rows = np.arange(nrows, dtype=np.int64) if rows is None else np.asarray(rows, dtype=np.int64)
     out = np.empty(len(rows) * ncols, np.uint16)
 
     def fn(lo, hi):
         idx = _flat_index(rows, ncols, lo, hi)
         z = _normal_flat(seed, stream, idx)
-        chi2 = sum(_normal_flat(seed, stream + 101 * (k + 1), idx) ** 2 for k in range(3))
+        chi2 = _normal_flat(seed, stream + 101, idx) ** 2 - 2.0 * np.log(_uniform(_stream_key(seed, stream + 202), idx))
         return f32_to_bf16_bits((sigma * z / np.sqrt(chi2 / 3.0)).astype(np.float32))
 
     _fill(fn, out.size, out)

@@ -1,0 +1,194 @@
+"""Thin Python binding of libswitchback (include/switchback.h): argument marshalling only.
+
+torch is used for device memory and the current HIP stream; every step of the layer runs in the library's HIP
+kernels.  There is no CPU or eager fallback: if the built library or the GPU is missing, the calls raise.
+
+Names follow the C ABI: quantize_rowwise, quantize_tensorwise, matmul_int8_dequant, forward, backward_input,
+backward_weight (Algorithm 1 of arxiv 2304.13013: X [b,n], W [m,n], Y/dY [b,m]).
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libswitchback.so")
+
+SB_BF16, SB_F32, SB_I32_RAW = 0, 1, 2
+SB_OP_QUANTIZE_TENSORWISE, SB_OP_FORWARD, SB_OP_BACKWARD_INPUT, SB_OP_BACKWARD_WEIGHT = 0, 1, 2, 3
+
+_TORCH_DTYPE = {SB_BF16: torch.bfloat16, SB_F32: torch.float32, SB_I32_RAW: torch.int32}
+_SB_DTYPE = {v: k for k, v in _TORCH_DTYPE.items()}
+
+
+class SbSaved(ctypes.Structure):
+    _fields_ = [("xq", ctypes.c_void_p), ("state_x", ctypes.c_void_p), ("wq", ctypes.c_void_p),
+                ("wq_t", ctypes.c_void_p), ("state_w", ctypes.c_void_p)]
+
+
+class SwitchBackError(RuntimeError):
+    pass
+
+
+_lib = None
+
+
+def load_library():
+    """dlopen the in-tree library and declare the C ABI.  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise SwitchBackError("libswitchback.so is not built: run `python -c 'import __graft_entry__ as g; "
+                              "g.build()'` (or paper_2304_13013_amd/build.py) first")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i64, sz, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_size_t, ctypes.c_int
+    lib.switchback_quantize_rowwise.argtypes = [vp, i64, i64, vp, vp, vp]
+    lib.switchback_quantize_tensorwise.argtypes = [vp, i64, i64, vp, vp, vp, vp, sz, vp]
+    lib.switchback_matmul_int8_dequant.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, ci, vp]
+    lib.switchback_forward.argtypes = [vp, vp, i64, i64, i64, vp, ci, ctypes.POINTER(SbSaved), vp, sz, vp]
+    lib.switchback_backward_input.argtypes = [vp, ctypes.POINTER(SbSaved), i64, i64, i64, vp, ci, vp, vp, vp]
+    lib.switchback_backward_weight.argtypes = [vp, vp, i64, i64, i64, vp, ci, vp, sz, vp]
+    lib.switchback_workspace_bytes.argtypes = [ci, i64, i64, i64]
+    lib.switchback_workspace_bytes.restype = sz
+    lib.switchback_status_string.argtypes = [ci]
+    lib.switchback_status_string.restype = ctypes.c_char_p
+    for name in ("switchback_quantize_rowwise", "switchback_quantize_tensorwise", "switchback_matmul_int8_dequant",
+                 "switchback_forward", "switchback_backward_input", "switchback_backward_weight"):
+        getattr(lib, name).restype = ci
+    _lib = lib
+    return lib
+
+
+def _check(status):
+    if status != 0:
+        raise SwitchBackError("libswitchback: %s (status %d)"
+                              % (load_library().switchback_status_string(status).decode(), status))
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t, dtype, ndim=None):
+    if not t.is_cuda:
+        raise SwitchBackError("tensors must live on the GPU")
+    if t.dtype != dtype or not t.is_contiguous() or (ndim is not None and t.dim() != ndim):
+        raise SwitchBackError("expected a contiguous %d-d %s tensor, got %s %s"
+                              % (ndim or t.dim(), dtype, tuple(t.shape), t.dtype))
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr() if t is not None else None)
+
+
+def workspace_bytes(op, b, n, m):
+    return int(load_library().switchback_workspace_bytes(op, b, n, m))
+
+
+def _workspace(op, b, n, m, device):
+    # Never zero-sized, so that the pointer is a valid aligned device address.
+    return torch.empty(max(workspace_bytes(op, b, n, m), 16), dtype=torch.uint8, device=device)
+
+
+def quantize_rowwise(x, q=None, state=None):
+    """Q_row(x), state_row(x) for a bf16 [rows, cols] tensor -> (int8 [rows, cols], f32 [rows])."""
+    lib = load_library()
+    xp = _dev(x, torch.bfloat16, 2)
+    rows, cols = x.shape
+    q = torch.empty((rows, cols), dtype=torch.int8, device=x.device) if q is None else q
+    state = torch.empty(rows, dtype=torch.float32, device=x.device) if state is None else state
+    _check(lib.switchback_quantize_rowwise(xp, rows, cols, _dev(q, torch.int8), _dev(state, torch.float32),
+                                           _stream()))
+    return q, state
+
+
+def quantize_tensorwise(w, q=None, q_t=None, state=None, ws=None, transpose=True):
+    """Q_tensor(w), Q_tensor(w)^T, state_tensor(w) for a bf16 [rows, cols] tensor."""
+    lib = load_library()
+    wp = _dev(w, torch.bfloat16, 2)
+    rows, cols = w.shape
+    q = torch.empty((rows, cols), dtype=torch.int8, device=w.device) if q is None else q
+    if transpose and q_t is None:
+        q_t = torch.empty((cols, rows), dtype=torch.int8, device=w.device)
+    state = torch.empty(1, dtype=torch.float32, device=w.device) if state is None else state
+    ws = _workspace(SB_OP_QUANTIZE_TENSORWISE, 0, cols, rows, w.device) if ws is None else ws
+    _check(lib.switchback_quantize_tensorwise(wp, rows, cols, _dev(q, torch.int8),
+                                              _dev(q_t, torch.int8) if q_t is not None else None,
+                                              _dev(state, torch.float32), _ptr(ws), ws.numel(), _stream()))
+    return q, q_t, state
+
+
+def matmul_int8_dequant(aq, state_row, bq, state_tensor, out_dtype=torch.bfloat16, out=None):
+    """out[i,j] = state_tensor/127^2 * state_row[i] * sum_k aq[i,k] bq[j,k]; int32 accumulators if out_dtype is
+    torch.int32 (the states may then be None)."""
+    lib = load_library()
+    M, K = aq.shape
+    N = bq.shape[0]
+    if bq.shape[1] != K:
+        raise SwitchBackError("contraction lengths differ")
+    out = torch.empty((M, N), dtype=out_dtype, device=aq.device) if out is None else out
+    _check(lib.switchback_matmul_int8_dequant(
+        _dev(aq, torch.int8, 2), _dev(state_row, torch.float32) if state_row is not None else None,
+        _dev(bq, torch.int8, 2), _dev(state_tensor, torch.float32) if state_tensor is not None else None,
+        M, N, K, _dev(out, out_dtype, 2), _SB_DTYPE[out_dtype], _stream()))
+    return out
+
+
+class LayerBuffers:
+    """Device buffers of one SwitchBack layer of shape (b, n, m), allocated once: what forward saves for
+    backward (int8 codes and states), the quantized dY, and the workspaces."""
+
+    def __init__(self, b, n, m, device="cuda"):
+        self.b, self.n, self.m = b, n, m
+        e = lambda shape, dt: torch.empty(shape, dtype=dt, device=device)
+        self.xq, self.state_x = e((b, n), torch.int8), e((b,), torch.float32)
+        self.wq, self.wq_t, self.state_w = e((m, n), torch.int8), e((n, m), torch.int8), e((1,), torch.float32)
+        self.gq, self.state_g = e((b, m), torch.int8), e((b,), torch.float32)
+        self.ws_fwd = _workspace(SB_OP_FORWARD, b, n, m, device)
+        self.ws_dw = _workspace(SB_OP_BACKWARD_WEIGHT, b, n, m, device)
+        self.saved = SbSaved(self.xq.data_ptr(), self.state_x.data_ptr(), self.wq.data_ptr(),
+                             self.wq_t.data_ptr(), self.state_w.data_ptr())
+
+
+def forward(x, w, bufs=None, y=None, y_dtype=torch.bfloat16):
+    """Algorithm 1 forward.  Returns (y [b,m], bufs); bufs holds xq, state_x, wq, wq_t, state_w."""
+    lib = load_library()
+    b, n = x.shape
+    m = w.shape[0]
+    if w.shape[1] != n:
+        raise SwitchBackError("x [b,n] and w [m,n] disagree on n")
+    bufs = LayerBuffers(b, n, m, x.device) if bufs is None else bufs
+    y = torch.empty((b, m), dtype=y_dtype, device=x.device) if y is None else y
+    _check(lib.switchback_forward(_dev(x, torch.bfloat16, 2), _dev(w, torch.bfloat16, 2), b, n, m,
+                                  _dev(y, y_dtype, 2), _SB_DTYPE[y_dtype], ctypes.byref(bufs.saved),
+                                  _ptr(bufs.ws_fwd), bufs.ws_fwd.numel(), _stream()))
+    return y, bufs
+
+
+def backward_input(dy, bufs, dx=None, dx_dtype=torch.bfloat16):
+    """Algorithm 1 input gradient.  Returns dx [b,n]; fills bufs.gq and bufs.state_g."""
+    lib = load_library()
+    b, m = dy.shape
+    n = bufs.n
+    dx = torch.empty((b, n), dtype=dx_dtype, device=dy.device) if dx is None else dx
+    _check(lib.switchback_backward_input(_dev(dy, torch.bfloat16, 2), ctypes.byref(bufs.saved), b, n, m,
+                                         _dev(dx, dx_dtype, 2), _SB_DTYPE[dx_dtype], _ptr(bufs.gq),
+                                         _ptr(bufs.state_g), _stream()))
+    return dx
+
+
+def backward_weight(dy, x, bufs=None, dw=None, dw_dtype=torch.bfloat16):
+    """Algorithm 1 weight gradient dW = dY^T X (bf16 operands, binary32 accumulation).  Returns dw [m,n]."""
+    lib = load_library()
+    b, m = dy.shape
+    n = x.shape[1]
+    if x.shape[0] != b:
+        raise SwitchBackError("dy [b,m] and x [b,n] disagree on b")
+    ws = bufs.ws_dw if bufs is not None else _workspace(SB_OP_BACKWARD_WEIGHT, b, n, m, dy.device)
+    dw = torch.empty((m, n), dtype=dw_dtype, device=dy.device) if dw is None else dw
+    _check(lib.switchback_backward_weight(_dev(dy, torch.bfloat16, 2), _dev(x, torch.bfloat16, 2), b, n, m,
+                                          _dev(dw, dw_dtype, 2), _SB_DTYPE[dw_dtype], _ptr(ws), ws.numel(),
+                                          _stream()))
+    return dw

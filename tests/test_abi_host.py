@@ -1,0 +1,88 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every function include/switchback.h
+declares, sizes workspaces, and rejects bad arguments before any kernel launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2304_13013_amd import switchback as sb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(sb.LIB_PATH):
+        from paper_2304_13013_amd import build
+        build.build()
+    return sb.load_library()
+
+
+def declared_functions():
+    with open(os.path.join(ROOT, "include", "switchback.h")) as fh:
+        text = re.sub(r"/\*.*?\*/", "", fh.read(), flags=re.S)
+    return sorted(set(re.findall(r"\b(switchback_\w+)\s*\(", text)))
+
+
+def test_exports_every_declared_symbol(lib):
+    names = declared_functions()
+    assert {"switchback_quantize_rowwise", "switchback_quantize_tensorwise", "switchback_forward",
+            "switchback_backward_input", "switchback_backward_weight"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), name
+
+
+def test_status_strings(lib):
+    seen = {lib.switchback_status_string(i).decode() for i in range(5)}
+    assert len(seen) == 5 and "ok" in seen
+    assert "unknown" in lib.switchback_status_string(99).decode()
+
+
+def test_workspace_sizes(lib):
+    assert sb.workspace_bytes(sb.SB_OP_FORWARD, 512, 256, 1024) >= 4096
+    assert sb.workspace_bytes(sb.SB_OP_QUANTIZE_TENSORWISE, 0, 256, 1024) >= 4096
+    assert sb.workspace_bytes(sb.SB_OP_BACKWARD_INPUT, 512, 256, 1024) == 0
+    big = sb.workspace_bytes(sb.SB_OP_BACKWARD_WEIGHT, 32896, 1280, 1280)
+    assert big % (1280 * 1280 * 4) == 0          # whole binary32 partial matrices
+    assert sb.workspace_bytes(sb.SB_OP_BACKWARD_WEIGHT, 16384, 4096, 16384) == 0  # enough tiles, no split
+    assert sb.workspace_bytes(99, 1, 64, 64) == 0
+
+
+def test_bad_arguments_are_rejected_before_launch(lib):
+    """Every call below must return an error code without touching the GPU (there is none on the build box)."""
+    fake = ctypes.c_void_p(0x1000)               # aligned, never dereferenced on the host
+    odd = ctypes.c_void_p(0x1004)
+    null = ctypes.c_void_p(None)
+    saved = sb.SbSaved(0x1000, 0x1000, 0x1000, 0x1000, 0x1000)
+    sp = ctypes.byref(saved)
+    INVALID, SHAPE, WS = 1, 2, 3
+    assert lib.switchback_quantize_rowwise(null, 4, 64, fake, fake, null) == INVALID
+    assert lib.switchback_quantize_rowwise(odd, 4, 64, fake, fake, null) == INVALID
+    assert lib.switchback_quantize_rowwise(fake, -1, 64, fake, fake, null) == INVALID
+    assert lib.switchback_quantize_rowwise(fake, 4, 60, fake, fake, null) == SHAPE
+    assert lib.switchback_quantize_rowwise(fake, 4, 1 << 20, fake, fake, null) == SHAPE
+    assert lib.switchback_quantize_rowwise(null, 0, 64, null, null, null) == 0       # empty input: no-op
+    assert lib.switchback_quantize_tensorwise(fake, 64, 64, fake, fake, fake, fake, 16, null) == WS
+    assert lib.switchback_quantize_tensorwise(fake, 64, 72, fake, fake, fake, fake, 1 << 20, null) == SHAPE
+    assert lib.switchback_quantize_tensorwise(fake, 64, 64, fake, odd, fake, fake, 1 << 20, null) == INVALID
+    assert lib.switchback_matmul_int8_dequant(fake, fake, fake, fake, 8, 64, 32, fake, 0, null) == SHAPE
+    assert lib.switchback_matmul_int8_dequant(fake, fake, fake, fake, 8, 64, 1 << 18, fake, 0, null) == SHAPE
+    assert lib.switchback_matmul_int8_dequant(fake, null, fake, fake, 8, 64, 64, fake, 0, null) == INVALID
+    assert lib.switchback_matmul_int8_dequant(fake, fake, fake, fake, 8, 64, 64, fake, 7, null) == INVALID
+    assert lib.switchback_forward(fake, fake, 8, 100, 64, fake, 0, sp, fake, 1 << 20, null) == SHAPE
+    assert lib.switchback_forward(fake, fake, 8, 64, 64, fake, 0, None, fake, 1 << 20, null) == INVALID
+    assert lib.switchback_forward(fake, fake, 8, 64, 64, fake, 0, sp, fake, 8, null) == WS
+    assert lib.switchback_forward(null, fake, 8, 64, 64, fake, 0, sp, fake, 1 << 20, null) == INVALID
+    assert lib.switchback_backward_input(fake, sp, 8, 64, 96, fake, 0, fake, fake, null) == SHAPE
+    assert lib.switchback_backward_input(null, sp, 8, 64, 64, fake, 0, fake, fake, null) == INVALID
+    assert lib.switchback_backward_input(null, sp, 0, 64, 64, null, 0, null, null, null) == 0   # b = 0
+    assert lib.switchback_backward_weight(fake, fake, 8, 64, 64, fake, 2, fake, 1 << 30, null) == INVALID
+    assert lib.switchback_backward_weight(fake, fake, 32896, 1280, 1280, fake, 0, fake, 64, null) == WS
+    assert lib.switchback_backward_weight(fake, fake, 8, 64, 64, null, 0, fake, 1 << 30, null) == INVALID
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    with pytest.raises(sb.SwitchBackError):
+        sb.quantize_rowwise(torch.zeros(4, 64, dtype=torch.bfloat16))

@@ -1,0 +1,273 @@
+"""GPU parity: every step of the SwitchBack layer, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Bars: int8 codes, states and int32 accumulators bit-exact; dequantized outputs within 1 binary32
+ulp before the bf16 cast (bf16 outputs must be the rounding of a value within that ulp); weight gradient
+max-abs error <= 1e-2 * rms(dW) in binary32 output mode."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2304_13013_amd import inputs as I
+from paper_2304_13013_amd import switchback as sb
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def to_dev(bits):
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(DEV).view(torch.bfloat16)
+
+
+def bits_of(t):
+    return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+
+
+def host(t):
+    return t.detach().cpu().numpy()
+
+
+def ulp(ref):
+    return np.spacing(np.abs(ref).astype(np.float32))
+
+
+def assert_bf16_is_rounding_within_one_ulp(got_bits, ref32, oracle):
+    """The bf16 result must equal RNE(v) for some v in {ref - 1ulp, ref, ref + 1ulp}."""
+    u = ulp(ref32)
+    cands = [oracle.round_to_bf16(ref32), oracle.round_to_bf16(ref32 - u), oracle.round_to_bf16(ref32 + u)]
+    ok = (got_bits == cands[0]) | (got_bits == cands[1]) | (got_bits == cands[2])
+    assert ok.all(), "%d bf16 outputs are not the rounding of a value within 1 ulp" % int((~ok).sum())
+
+
+def rand_bf16(rng, shape, scale=1.0):
+    return I.f32_to_bf16_bits((rng.standard_normal(shape) * scale).astype(np.float32))
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# quantizers
+# ---------------------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("rows,cols", [
+    (512, 256), (1, 8), (3, 64), (5, 520), (257, 1280), (66, 2048), (9, 2056), (130, 3072), (33, 5120),
+    (7, 8192), (5, 12296), (6, 16384), (3, 16392), (2, 65536)])
+def test_quantize_rowwise(oracle, rows, cols):
+    x = rand_bf16(np.random.default_rng(rows * 131 + cols), (rows, cols), 2.0)
+    if rows >= 8:
+        I.plant_edge_rows(x)
+    q, s = sb.quantize_rowwise(to_dev(x))
+    torch.cuda.synchronize()
+    qo, so = oracle.quantize_rowwise(x)
+    np.testing.assert_array_equal(host(s).view(np.uint32), so.view(np.uint32))
+    np.testing.assert_array_equal(host(q), qo)
+
+
+def test_quantize_rowwise_empty():
+    x = torch.empty((0, 64), dtype=torch.bfloat16, device=DEV)
+    q, s = sb.quantize_rowwise(x)
+    assert q.shape == (0, 64) and s.shape == (0,)
+
+
+@pytest.mark.parametrize("rows,cols", [(1024, 256), (16, 16), (64, 64), (272, 144), (128, 128), (1280, 5120),
+                                       (144, 4096 + 16)])
+def test_quantize_tensorwise(oracle, rows, cols):
+    w = rand_bf16(np.random.default_rng(rows + 7 * cols), (rows, cols), 0.05)
+    q, q_t, s = sb.quantize_tensorwise(to_dev(w))
+    torch.cuda.synchronize()
+    qo, qto, so = oracle.quantize_tensorwise(w)
+    assert host(s).view(np.uint32)[0] == np.float32(so).view(np.uint32)
+    np.testing.assert_array_equal(host(q), qo)
+    np.testing.assert_array_equal(host(q_t), qto)
+    q2, none, s2 = sb.quantize_tensorwise(to_dev(w), transpose=False)
+    torch.cuda.synchronize()
+    assert none is None
+    np.testing.assert_array_equal(host(q2), qo)
+
+
+def test_quantize_tensorwise_degenerate(oracle):
+    for w in (np.zeros((64, 64), np.uint16), I.f32_to_bf16_bits(np.full((32, 48), 1e-38, np.float32))):
+        q, q_t, s = sb.quantize_tensorwise(to_dev(w))
+        torch.cuda.synchronize()
+        assert s.item() == 0 and not host(q).any() and not host(q_t).any()
+    ties = np.zeros((16, 16), np.float32)
+    ties[0, :9] = [1, 3, 5, 7, -1, -3, -5, -7, 254]
+    q, _, s = sb.quantize_tensorwise(to_dev(I.f32_to_bf16_bits(ties)))
+    torch.cuda.synchronize()
+    assert s.item() == 254 and host(q)[0, :9].tolist() == [0, 2, 2, 4, 0, -2, -2, -4, 127]
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# int8 product: raw accumulators, then dequantized
+# ---------------------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("M,N,K", [(512, 1024, 256), (300, 320, 192), (1, 64, 64), (257, 64, 128),
+                                   (700, 832, 448), (513, 256, 1280), (31, 576, 64)])
+def test_int8_accumulators_bit_exact(oracle, M, N, K):
+    rng = np.random.default_rng(M + N + K)
+    a = rng.integers(-127, 128, size=(M, K)).astype(np.int8)
+    b = rng.integers(-127, 128, size=(N, K)).astype(np.int8)
+    acc = sb.matmul_int8_dequant(torch.from_numpy(a).to(DEV), None, torch.from_numpy(b).to(DEV), None,
+                                 out_dtype=torch.int32)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host(acc), oracle.matmul_int8(a, b))
+
+
+def test_int8_accumulator_extremes(oracle):
+    """Longest supported contraction with all codes at +-127: |acc| = 127^2 * 131072 still fits int32."""
+    K = 131072
+    a = np.full((64, K), 127, np.int8)
+    a[1::2] = -127
+    b = np.full((64, K), 127, np.int8)
+    acc = host(sb.matmul_int8_dequant(torch.from_numpy(a).to(DEV), None, torch.from_numpy(b).to(DEV), None,
+                                      out_dtype=torch.int32))
+    assert (acc[0::2] == 16129 * K).all() and (acc[1::2] == -16129 * K).all()
+
+
+@pytest.mark.parametrize("M,N,K", [(300, 320, 192), (512, 256, 1024)])
+def test_dequantized_product(oracle, M, N, K):
+    rng = np.random.default_rng(M * 3 + N)
+    a = rng.integers(-127, 128, size=(M, K)).astype(np.int8)
+    b = rng.integers(-127, 128, size=(N, K)).astype(np.int8)
+    srow = (rng.random(M) * 4 + 1e-3).astype(np.float32)
+    srow[M // 2] = 0.0
+    sw = np.array([0.21875], np.float32)
+    args = (torch.from_numpy(a).to(DEV), torch.from_numpy(srow).to(DEV), torch.from_numpy(b).to(DEV),
+            torch.from_numpy(sw).to(DEV))
+    y32 = host(sb.matmul_int8_dequant(*args, out_dtype=torch.float32))
+    ybf = bits_of(sb.matmul_int8_dequant(*args, out_dtype=torch.bfloat16))
+    ref = oracle.dequantize(oracle.matmul_int8(a, b), srow, sw[0])
+    assert np.all(np.abs(y32 - ref) <= ulp(ref))
+    assert not y32[M // 2].any()
+    assert_bf16_is_rounding_within_one_ulp(ybf, ref, oracle)
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# the layer: tiny config, everything compared in full
+# ---------------------------------------------------------------------------------------------------------------
+
+def check_layer_full(oracle, d):
+    x, w, dy = to_dev(d["x"]), to_dev(d["w"]), to_dev(d["dy"])
+    y32, bufs = sb.forward(x, w, y_dtype=torch.float32)
+    ybf, _ = sb.forward(x, w, bufs=bufs, y_dtype=torch.bfloat16)
+    acc, _ = sb.forward(x, w, bufs=bufs, y_dtype=torch.int32)
+    dx32 = sb.backward_input(dy, bufs, dx_dtype=torch.float32)
+    dxbf = sb.backward_input(dy, bufs, dx_dtype=torch.bfloat16)
+    dacc = sb.backward_input(dy, bufs, dx_dtype=torch.int32)
+    dw32 = sb.backward_weight(dy, x, bufs, dw_dtype=torch.float32)
+    dwbf = sb.backward_weight(dy, x, bufs, dw_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+
+    f = oracle.forward(d["x"], d["w"])
+    np.testing.assert_array_equal(host(bufs.xq), f["xq"])
+    np.testing.assert_array_equal(host(bufs.state_x).view(np.uint32), f["state_x"].view(np.uint32))
+    np.testing.assert_array_equal(host(bufs.wq), f["wq"])
+    np.testing.assert_array_equal(host(bufs.wq_t), f["wq_t"])
+    assert host(bufs.state_w).view(np.uint32)[0] == np.float32(f["state_w"]).view(np.uint32)
+    np.testing.assert_array_equal(host(acc), f["acc"])
+    assert np.all(np.abs(host(y32) - f["y32"]) <= ulp(f["y32"]))
+    assert_bf16_is_rounding_within_one_ulp(bits_of(ybf), f["y32"], oracle)
+
+    g = oracle.backward_input(d["dy"], f["wq_t"], f["state_w"])
+    np.testing.assert_array_equal(host(bufs.gq), g["gq"])
+    np.testing.assert_array_equal(host(bufs.state_g).view(np.uint32), g["state_g"].view(np.uint32))
+    np.testing.assert_array_equal(host(dacc), g["acc"])
+    assert np.all(np.abs(host(dx32) - g["dx32"]) <= ulp(g["dx32"]))
+    assert_bf16_is_rounding_within_one_ulp(bits_of(dxbf), g["dx32"], oracle)
+
+    h = oracle.backward_weight(d["dy"], d["x"])
+    rms = float(np.sqrt((h["dw64"] ** 2).mean()))
+    got = host(dw32)
+    assert np.abs(got.astype(np.float64) - h["dw64"]).max() <= 1e-2 * rms
+    # bf16 mode: the rounding of the library's own binary32 result, hence within one bf16 ulp of the oracle's
+    np.testing.assert_array_equal(bits_of(dwbf), oracle.round_to_bf16(got))
+    return f, g, h
+
+
+def test_layer_tiny_with_edge_rows(oracle):
+    d = I.make_layer_inputs("tiny")
+    I.plant_edge_rows(d["x"])
+    I.plant_edge_rows(d["dy"])
+    f, g, h = check_layer_full(oracle, d)
+    assert not f["y32"][0].any() and not f["y32"][1].any()       # zero row and overflow row -> zero output
+
+
+@pytest.mark.parametrize("b,n,m", [(1, 64, 64), (33, 192, 320), (197, 320, 64), (300, 128, 576), (1000, 64, 256)])
+def test_layer_ragged_shapes(oracle, b, n, m):
+    rng = np.random.default_rng(b + n + m)
+    d = dict(x=rand_bf16(rng, (b, n)), w=rand_bf16(rng, (m, n), n ** -0.5), dy=rand_bf16(rng, (b, m), 0.1))
+    check_layer_full(oracle, d)
+
+
+def test_layer_empty_batch():
+    w = to_dev(rand_bf16(np.random.default_rng(0), (64, 64), 0.1))
+    x = torch.empty((0, 64), dtype=torch.bfloat16, device=DEV)
+    y, bufs = sb.forward(x, w)
+    dx = sb.backward_input(torch.empty((0, 64), dtype=torch.bfloat16, device=DEV), bufs)
+    dw = sb.backward_weight(torch.empty((0, 64), dtype=torch.bfloat16, device=DEV), x, bufs, dw_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert y.shape == (0, 64) and dx.shape == (0, 64) and not host(dw).any()
+    assert bufs.state_w.item() > 0                                # W is still quantized
+
+
+def test_results_are_deterministic():
+    d = I.make_layer_inputs("tiny")
+    x, w, dy = to_dev(d["x"]), to_dev(d["w"]), to_dev(d["dy"])
+    outs = []
+    for _ in range(3):
+        y, bufs = sb.forward(x, w)
+        dx = sb.backward_input(dy, bufs)
+        dw = sb.backward_weight(dy, x, bufs, dw_dtype=torch.float32)
+        torch.cuda.synchronize()
+        outs.append((bits_of(y), bits_of(dx), host(dw).copy()))
+    for o in outs[1:]:
+        assert all(np.array_equal(a, b) for a, b in zip(o, outs[0]))
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# full-size configurations, in the launch configuration the benchmark times: quantizers compared in full,
+# products on sampled rows the oracle computes one by one
+# ---------------------------------------------------------------------------------------------------------------
+
+FULL = [("vit_b16", 0), ("vit_b16", 1), ("vit_l14", 1), ("vit_l14", 3), ("vit_h14", 0), ("vit_h14", 1),
+        ("vit_h14", 2), ("vit_h14", 3), ("outlier", 0), ("outlier", 1)]
+
+
+@pytest.mark.parametrize("config,layer", FULL)
+def test_layer_full_size_sampled(oracle, config, layer):
+    L = I.CONFIGS[config].layers[layer]
+    d = I.make_layer_inputs(config, layer)
+    x, w, dy = to_dev(d["x"]), to_dev(d["w"]), to_dev(d["dy"])
+    bufs = sb.LayerBuffers(L.b, L.n, L.m, DEV)
+    y32, _ = sb.forward(x, w, bufs=bufs, y_dtype=torch.float32)
+    ybf, _ = sb.forward(x, w, bufs=bufs, y_dtype=torch.bfloat16)
+    dxbf = sb.backward_input(dy, bufs, dx_dtype=torch.bfloat16)
+    dw32 = sb.backward_weight(dy, x, bufs, dw_dtype=torch.float32)
+    torch.cuda.synchronize()
+
+    # quantizers: every element
+    xq, sx = oracle.quantize_rowwise(d["x"])
+    np.testing.assert_array_equal(host(bufs.state_x).view(np.uint32), sx.view(np.uint32))
+    np.testing.assert_array_equal(host(bufs.xq), xq)
+    wq, wq_t, sw = oracle.quantize_tensorwise(d["w"])
+    assert host(bufs.state_w).view(np.uint32)[0] == np.float32(sw).view(np.uint32)
+    np.testing.assert_array_equal(host(bufs.wq), wq)
+    np.testing.assert_array_equal(host(bufs.wq_t), wq_t)
+    gq, sg = oracle.quantize_rowwise(d["dy"])
+    np.testing.assert_array_equal(host(bufs.state_g).view(np.uint32), sg.view(np.uint32))
+    np.testing.assert_array_equal(host(bufs.gq), gq)
+
+    # products: sampled token rows (first, last, tile edges, random)
+    rng = np.random.default_rng(17)
+    rows = np.unique(np.concatenate([[0, 1, 255, 256, L.b - 257, L.b - 256, L.b - 2, L.b - 1],
+                                     rng.integers(0, L.b, 24)]))
+    ref = oracle.dequantize(oracle.matmul_int8(xq[rows], wq), sx[rows], sw)
+    idx = torch.from_numpy(rows).to(DEV)
+    assert np.all(np.abs(host(y32[idx]) - ref) <= ulp(ref))
+    assert_bf16_is_rounding_within_one_ulp(bits_of(ybf[idx]), ref, oracle)
+    ref = oracle.dequantize(oracle.matmul_int8(gq[rows], wq_t), sg[rows], sw)
+    assert_bf16_is_rounding_within_one_ulp(bits_of(dxbf[idx]), ref, oracle)
+
+    # weight gradient: sampled dW rows (columns of dY), full contraction
+    jrows = np.unique(np.concatenate([[0, 255, 256, L.m - 1], rng.integers(0, L.m, 4)]))
+    dw_ref = oracle.weight_grad(np.ascontiguousarray(d["dy"][:, jrows]), d["x"])
+    rms = float(np.sqrt((dw_ref ** 2).mean()))
+    got = host(dw32[torch.from_numpy(jrows).to(DEV)]).astype(np.float64)
+    assert np.abs(got - dw_ref).max() <= 1e-2 * rms
