@@ -29,6 +29,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="vit_h14", help="workload (default: the headline ViT-H/14 shapes)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also launch three 256 MiB device-to-device copy kernels (known traffic) so that a "
+                         "rocprofv3 --pmc run of this command can scale FETCH_SIZE / WRITE_SIZE")
     ap.add_argument("--cpu-sample-rows", type=int, default=0, help="token rows of the oracle sample (0 = auto)")
     return ap.parse_args()
 
@@ -154,12 +157,20 @@ def main():
     op_sum = sum(k["ms_per_step"] for k in kernels.values())
     quant_ms = kernels["quantize_rowwise"]["ms_per_step"] + kernels["quantize_tensorwise"]["ms_per_step"]
 
+    if args.copy_calibration:
+        src = torch.ones(128 << 20, dtype=torch.bfloat16, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     # ---- CPU oracle on a bounded sample of the same workload --------------------------------------------------
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import switchback_oracle as oracle
         L = max(cfg.layers, key=lambda l: l.n * l.m)
-        rows = args.cpu_sample_rows or max(8, int(6.0e9 / (3.0 * L.n * L.m)))
+        rows = args.cpu_sample_rows or max(8, int(1.5e11 / (3.0 * L.n * L.m)))
         rows = min(rows, L.b)
         idx = np.linspace(0, L.b - 1, rows).astype(np.int64)
         li = cfg.layers.index(L)

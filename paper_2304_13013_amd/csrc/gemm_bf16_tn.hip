@@ -48,7 +48,13 @@ __global__ __launch_bounds__(THREADS) void gemm_bf16_tn_kernel(GemmBf16Args p) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm0 = (wave / WAVES_N) * WTM, wn0 = (wave % WAVES_N) * WTN;
 
-    const int tile = blockIdx.x / p.splits, split = blockIdx.x % p.splits;
+    // Workgroups are dealt to the 8 XCDs round-robin; give each XCD a contiguous run of (split, tile) work items in
+    // split-major order, so that the workgroups sharing an L2 read the same token range of dY and X.
+    const int total = p.tiles_m * p.tiles_n * p.splits;
+    const int per_xcd = (total + 7) / 8;
+    const int item = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (item >= total || (int)(blockIdx.x >> 3) >= per_xcd) return;  // uniform per workgroup
+    const int split = item / (p.tiles_m * p.tiles_n), tile = item % (p.tiles_m * p.tiles_n);
     const int tm = tile / p.tiles_n, tn = tile % p.tiles_n;
     const int k_begin = split * p.k_per_split;
     const int k_end = min(p.b, k_begin + p.k_per_split);
@@ -197,7 +203,8 @@ hipError_t launch_gemm_bf16_tn(const void *dy, const void *x, int64_t b, int64_t
     a.partial = static_cast<float *>(ws);
     a.out = dw;
     a.out_bf16 = dw_dtype == SB_BF16;
-    gemm_bf16_tn_kernel<<<a.tiles_m * a.tiles_n * a.splits, THREADS, 0, stream>>>(a);
+    const int total = a.tiles_m * a.tiles_n * a.splits;
+    gemm_bf16_tn_kernel<<<8 * ((total + 7) / 8), THREADS, 0, stream>>>(a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || a.splits == 1) return e;
     const int64_t quads = m * n / 4;

@@ -1,0 +1,337 @@
+// int8 x int8 -> int32 GEMM kernel with the dequantizing epilogue of the SwitchBack forward / input-gradient
+// products (the dequantized forward equation of Section 2.2.1 of arxiv 2304.13013), hand-written for gfx950.
+//
+//   out[i,j] = (state_tensor/127^2 * state_row[i]) * sum_k aq[i,k] * bq[j,k]        aq [M,K], bq [N,K], K contiguous
+//
+// Design
+//   * v_mfma_i32_32x32x32_i8.  The weight-side tile (bq rows) is the MFMA's first operand and the token-side
+//     tile (aq rows) its second, so a lane ends up owning ONE output row (lane % 32) and, per accumulator quad,
+//     four consecutive output columns: one row scale per lane, and packed bf16x4 leaves each quad.
+//   * A persistent grid (one workgroup per compute unit) walks the output tiles in an order that keeps the
+//     workgroups of one XCD (workgroup id % 8) on a compact patch of tiles, so its L2 sees each operand panel once.
+//   * Operand tiles go HBM/L2 -> LDS with global_load_lds_dwordx4 (no VGPR staging), STAGES deep.  One wave
+//     instruction fills 1 KiB of LDS linearly, so the bank-conflict-avoiding swizzle is applied on the GLOBAL side:
+//     LDS slot (row, p) holds 16-byte k-chunk p ^ f(row) of that row, f(row) = (row / (256/BK)) % (BK/16).
+//   * MFMA operand fragments are double-buffered in registers: the ds_reads of k-step j+1 are issued before the
+//     MFMAs of k-step j, also across the stage boundary (the stage hand-over barrier sits between the last
+//     fragment read of a stage and its last MFMAs).
+//   * The next tile's first STAGES-1 stages are requested BEFORE the epilogue of the current tile.  The epilogue
+//     transposes the bf16 results through the one LDS stage those requests leave free (wave-private, XOR
+//     swizzled) and stores 16 bytes per lane, covering whole 128-byte row segments.
+//   * Rows past M (and weight rows past N) are clamped on load and masked on store; an out-of-range row only ever
+//     feeds accumulators that are never stored.
+#pragma once
+#include "sb_common.h"
+
+namespace sb {
+
+enum { OUT_BF16 = 0, OUT_F32 = 1, OUT_I32 = 2 };
+
+template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int STAGES_, int EPI_OWN_ = 0, int NTS_ = 0, int DIAG_ = 0>
+struct GemmI8Cfg {
+    static constexpr int EPI_OWN = EPI_OWN_;  // 1: the epilogue patch has its own LDS region, 0: it borrows the last stage
+    static constexpr int NTS = NTS_;          // 1: non-temporal output stores
+    static constexpr int DIAG = DIAG_;  // 0 normal; timing diagnostics: 1 no global loads, 2 no MFMA/LDS reads, 3 all workgroups load tile (0,0)
+    static constexpr int BM = BM_, BN = BN_, BK = BK_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, STAGES = STAGES_;
+    static constexpr int NWAVES = WAVES_M * WAVES_N, THREADS = NWAVES * 64;
+    static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;  // wave tile
+    static constexpr int MT = WTM / 32, NT = WTN / 32;            // 32x32 MFMA blocks per wave tile
+    static constexpr int KK = BK / 32;                            // MFMA k-steps per stage
+    static constexpr int CPR = BK / 16;                           // 16-byte chunks per tile row
+    static constexpr int RPS = 1024 / BK;                         // tile rows per 1 KiB slab (one wave load)
+    static constexpr int SWZ_DIV = 256 / BK;                      // rows that share one 256-byte bank window
+    static constexpr int STAGE_BYTES = (BM + BN) * BK;
+    static constexpr int NSLAB = STAGE_BYTES / 1024;
+    static constexpr int LPW = NSLAB / NWAVES;                    // global->LDS loads per wave per stage
+    static constexpr int EPI_PIECES = WTN * 2 / 16;               // 16-byte pieces per row of the epilogue patch
+    static constexpr int EPI_WAVE_BYTES = 32 * WTN * 2;           // 32 rows of bf16 per wave
+    static constexpr int EPI_STORES = MT * (EPI_WAVE_BYTES / 1024);  // 16-byte global stores per lane per tile
+    static constexpr int NPRO = EPI_OWN ? STAGES : STAGES - 1;      // stages requested ahead of a tile's main loop
+    static constexpr int LDS_BYTES = STAGES * STAGE_BYTES + (EPI_OWN ? NWAVES * EPI_WAVE_BYTES : 0);
+    static_assert(BK == 64 || BK == 128, "BK");
+    static_assert(STAGES >= 2 && STAGES <= 5, "STAGES");
+    static_assert(WTM % 32 == 0 && WTN % 32 == 0 && NSLAB % NWAVES == 0 && KK % 2 == 0, "tile shape");
+    static_assert(EPI_WAVE_BYTES % 1024 == 0 && EPI_PIECES >= 8, "epilogue patch must be whole wave reads");
+    static_assert(NWAVES * EPI_WAVE_BYTES <= STAGE_BYTES && NPRO >= 1 && (EPI_OWN || STAGES >= 3), "epilogue patch");
+    static_assert(LPW * (NPRO - 1) + EPI_STORES < 64 && NPRO <= 4, "vmcnt range");
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS");
+};
+
+struct GemmI8Args {
+    const int8_t *a;
+    const int8_t *b;
+    const float *state_row;
+    const float *state_tensor;
+    void *out;
+    int M, N, K;
+    int tiles_m, tiles_n;
+    int group_m;  // tile rows per group of the tile walk
+};
+
+// Output tile visited by workgroup `wg` in its `round`-th iteration.  Workgroups are dealt to XCDs round-robin,
+// so the nwg/8 workgroups with equal wg % 8 share an L2; they get consecutive ids in an order that walks groups
+// of group_m tile-rows column by column.
+__device__ __forceinline__ bool gemm_tile_of(int wg, int round, int nwg, int tiles_m, int tiles_n, int group_m,
+                                             int *tm, int *tn) {
+    const int per_xcd = nwg >> 3;
+    const int id = (round * 8 + (wg & 7)) * per_xcd + (wg >> 3);
+    if (id >= tiles_m * tiles_n) return false;
+    const int per_group = group_m * tiles_n;
+    const int first_m = (id / per_group) * group_m;
+    const int group_rows = min(tiles_m - first_m, group_m);
+    const int r = id % per_group;
+    *tm = first_m + r % group_rows;
+    *tn = r / group_rows;
+    return true;
+}
+
+// Workgroup barrier WITHOUT the memory fence of __syncthreads(): the fence would drain every outstanding
+// global->LDS request (vmcnt(0)) and serialize the pipeline.  Explicit vmcnt / lgkmcnt waits order the LDS traffic.
+__device__ __forceinline__ void block_barrier() { asm volatile("s_barrier" ::: "memory"); }
+__device__ __forceinline__ void wait_lds_reads() { __builtin_amdgcn_s_waitcnt(0xC07F); }  // lgkmcnt(0) only
+
+// Wait until at most `later` stages (LPW loads each) plus, if `stores`, NST output stores remain outstanding.
+template <int LPW, int NST>
+__device__ __forceinline__ void wait_stage(int later, bool stores) {
+    if (stores) {
+        switch (later) {
+            case 0: wait_vmcnt<NST>(); break;
+            case 1: wait_vmcnt<LPW + NST>(); break;
+            case 2: wait_vmcnt<(2 * LPW + NST < 64 ? 2 * LPW + NST : 0)>(); break;
+            default: wait_vmcnt<(3 * LPW + NST < 64 ? 3 * LPW + NST : 0)>(); break;
+        }
+    } else {
+        switch (later) {
+            case 0: wait_vmcnt<0>(); break;
+            case 1: wait_vmcnt<LPW>(); break;
+            case 2: wait_vmcnt<(2 * LPW < 64 ? 2 * LPW : 0)>(); break;
+            default: wait_vmcnt<(3 * LPW < 64 ? 3 * LPW : 0)>(); break;
+        }
+    }
+}
+
+template <class C, int OUT>
+__global__ __launch_bounds__(C::THREADS) void gemm_i8_dequant_kernel(GemmI8Args p) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    typedef __attribute__((address_space(3))) void lds_void;
+    typedef const __attribute__((address_space(1))) void gbl_void;
+    constexpr int S = C::STAGES;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm0 = (wave / C::WAVES_N) * C::WTM, wn0 = (wave % C::WAVES_N) * C::WTN;
+    const int KT = p.K / C::BK;
+
+    // Per-lane byte offset of its MFMA operand chunk inside a 32-row block of a stage, one per k-step.
+    const int frow = lane & 31, fhalf = lane >> 5;
+    const int fswz = (frow / C::SWZ_DIV) % C::CPR;
+    int frag_off[C::KK];
+#pragma unroll
+    for (int kk = 0; kk < C::KK; ++kk) frag_off[kk] = frow * C::BK + (((kk * 2 + fhalf) ^ fswz) << 4);
+
+    // Loader role of this lane: slab s = wave*LPW + i covers stage rows [s*RPS, (s+1)*RPS).
+    const int lrow_in_slab = lane / C::CPR, lpos = lane % C::CPR;
+
+    const int8_t *gsrc[C::LPW];
+    auto set_tile_sources = [&](int tm, int tn) {
+        if (C::DIAG == 3) tm = tn = 0;
+#pragma unroll
+        for (int i = 0; i < C::LPW; ++i) {
+            const int srow = (wave * C::LPW + i) * C::RPS + lrow_in_slab;
+            const int chunk = lpos ^ ((srow / C::SWZ_DIV) % C::CPR);
+            if (srow < C::BM) {
+                const int r = min(tm * C::BM + srow, p.M - 1);
+                gsrc[i] = p.a + (int64_t)r * p.K + chunk * 16;
+            } else {
+                const int r = min(tn * C::BN + (srow - C::BM), p.N - 1);
+                gsrc[i] = p.b + (int64_t)r * p.K + chunk * 16;
+            }
+        }
+    };
+    auto issue_stage = [&](int kt) {
+        unsigned char *dst = smem + (kt % S) * C::STAGE_BYTES + wave * C::LPW * 1024;
+        if (C::DIAG == 1) return;
+#pragma unroll
+        for (int i = 0; i < C::LPW; ++i)
+            __builtin_amdgcn_global_load_lds((gbl_void *)(gsrc[i] + (int64_t)kt * C::BK), (lds_void *)(dst + i * 1024),
+                                             16, 0, 0);
+    };
+    auto issue_prologue = [&]() {
+#pragma unroll
+        for (int s = 0; s < C::NPRO; ++s)
+            if (s < KT) issue_stage(s);
+    };
+
+    v4i xf[2][C::MT], wf[2][C::NT];
+    auto read_frags = [&](int buf, int kt, int kk) {
+        if (C::DIAG == 2) return;
+        const unsigned char *xs = smem + (kt % S) * C::STAGE_BYTES + wm0 * C::BK + frag_off[kk];
+        const unsigned char *ws = smem + (kt % S) * C::STAGE_BYTES + (C::BM + wn0) * C::BK + frag_off[kk];
+#pragma unroll
+        for (int mt = 0; mt < C::MT; ++mt) xf[buf][mt] = *reinterpret_cast<const v4i *>(xs + mt * 32 * C::BK);
+#pragma unroll
+        for (int nt = 0; nt < C::NT; ++nt) wf[buf][nt] = *reinterpret_cast<const v4i *>(ws + nt * 32 * C::BK);
+    };
+
+    int tm, tn;
+    bool have = gemm_tile_of(blockIdx.x, 0, gridDim.x, p.tiles_m, p.tiles_n, p.group_m, &tm, &tn);
+    if (have) {
+        set_tile_sources(tm, tn);
+        issue_prologue();
+    }
+    // Whether the previous tile's EPI_STORES output stores sit right behind this tile's pre-requested stages in
+    // the vector-memory queue (false when unknown, which only makes the waits stricter).
+    bool stores_behind_prologue = false;
+
+    for (int round = 0; have; ++round) {
+        v16i acc[C::MT][C::NT];
+#pragma unroll
+        for (int mt = 0; mt < C::MT; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < C::NT; ++nt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[mt][nt][r] = 0;
+
+        // Stage 0 of this tile: behind it sit the other pre-requested stages (and the previous tile's stores).
+        int issued_upto = min(C::NPRO - 1, KT - 1);
+        wait_stage<C::LPW, C::EPI_STORES>(issued_upto, stores_behind_prologue);
+        block_barrier();
+        read_frags(0, 0, 0);
+
+        for (int kt = 0; kt < KT; ++kt) {
+#pragma unroll
+            for (int kk = 0; kk < C::KK; ++kk) {
+                if (kk + 1 < C::KK) {
+                    read_frags((kk + 1) & 1, kt, kk + 1);
+                } else if (kt + 1 < KT) {
+                    // Hand-over: every fragment of stage kt is in (or on its way to) registers.  Retire this
+                    // wave's LDS reads, make sure stage kt+1 has landed, then refill the freed stage(s).
+                    wait_stage<C::LPW, C::EPI_STORES>(issued_upto - (kt + 1), stores_behind_prologue && kt + 1 < C::NPRO);
+                    wait_lds_reads();
+                    block_barrier();
+                    if (!C::EPI_OWN && kt == 0 && S - 1 < KT) issue_stage(S - 1);  // the stage the last epilogue borrowed
+                    if (kt + S < KT) issue_stage(kt + S);
+                    issued_upto = min(KT - 1, kt + S);
+                    read_frags(0, kt + 1, 0);
+                }
+                if (C::DIAG != 2) {
+#pragma unroll
+                    for (int mt = 0; mt < C::MT; ++mt)
+#pragma unroll
+                        for (int nt = 0; nt < C::NT; ++nt)
+                            acc[mt][nt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[kk & 1][nt], xf[kk & 1][mt],
+                                                                                acc[mt][nt], 0, 0, 0);
+                }
+            }
+        }
+
+        const int m_base = tm * C::BM + wm0, n_base = tn * C::BN + wn0;
+        const bool interior = (tm + 1) * C::BM <= p.M && (tn + 1) * C::BN <= p.N;
+
+        // Row scales r_i = state_row[i] * (state_tensor / 127^2), one per lane per 32-row block.
+        float rscale[C::MT];
+        if (OUT != OUT_I32) {
+            const float c = p.state_tensor[0] / 16129.0f;
+#pragma unroll
+            for (int mt = 0; mt < C::MT; ++mt)
+                rscale[mt] = p.state_row[min(m_base + mt * 32 + frow, p.M - 1)] * c;
+            // Pin the scales (and the wait for their loads) in front of the requests issued below, so that the
+            // epilogue does not have to wait for the next tile's stages.
+#pragma unroll
+            for (int mt = 0; mt < C::MT; ++mt) asm volatile("" : "+v"(rscale[mt]));
+        }
+
+        // Every wave is done reading the stages: request the next tile's first stages, then run the epilogue
+        // while they are in flight.
+        wait_lds_reads();
+        block_barrier();
+        int ntm, ntn;
+        have = gemm_tile_of(blockIdx.x, round + 1, gridDim.x, p.tiles_m, p.tiles_n, p.group_m, &ntm, &ntn);
+        if (have) {
+            set_tile_sources(ntm, ntn);
+            issue_prologue();
+        }
+        // The wait counts of the next main loop assume these requests precede the output stores below.
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("" ::: "memory");
+
+        if (OUT == OUT_BF16) {
+            unsigned short *out = static_cast<unsigned short *>(p.out);
+            unsigned char *epi = smem + (C::EPI_OWN ? S : S - 1) * C::STAGE_BYTES + wave * C::EPI_WAVE_BYTES;
+#pragma unroll
+            for (int mt = 0; mt < C::MT; ++mt) {
+#pragma unroll
+                for (int nt = 0; nt < C::NT; ++nt)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        v4f v;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] = (float)acc[mt][nt][4 * g + e] * rscale[mt];
+                        const int piece = (nt * 4 + g) ^ (frow & 7);
+                        *reinterpret_cast<v4bf *>(epi + frow * (C::WTN * 2) + piece * 16 + fhalf * 8) =
+                            __builtin_convertvector(v, v4bf);
+                    }
+#pragma unroll
+                for (int j = 0; j < C::EPI_WAVE_BYTES / 1024; ++j) {
+                    const int idx = j * 64 + lane;
+                    const int prow = idx / C::EPI_PIECES, piece = idx % C::EPI_PIECES;
+                    const v4u val = *reinterpret_cast<const v4u *>(epi + prow * (C::WTN * 2) +
+                                                                   ((piece ^ (prow & 7)) << 4));
+                    const int gr = m_base + mt * 32 + prow, gc = n_base + piece * 8;
+                    if (interior || (gr < p.M && gc < p.N)) {
+                        if (C::NTS)
+                            __builtin_nontemporal_store(val, reinterpret_cast<v4u *>(out + (int64_t)gr * p.N + gc));
+                        else
+                            *reinterpret_cast<v4u *>(out + (int64_t)gr * p.N + gc) = val;
+                    }
+                }
+            }
+        } else {
+            // Verification paths: binary32 results or raw accumulators, stored straight from the registers.
+#pragma unroll
+            for (int mt = 0; mt < C::MT; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < C::NT; ++nt)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int gr = m_base + mt * 32 + frow, gc = n_base + nt * 32 + 8 * g + 4 * fhalf;
+                        if (gr < p.M && gc < p.N) {
+                            if (OUT == OUT_F32) {
+                                v4f v;
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) v[e] = (float)acc[mt][nt][4 * g + e] * rscale[mt];
+                                *reinterpret_cast<v4f *>(static_cast<float *>(p.out) + (int64_t)gr * p.N + gc) = v;
+                            } else {
+                                v4i v;
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) v[e] = acc[mt][nt][4 * g + e];
+                                *reinterpret_cast<v4i *>(static_cast<int *>(p.out) + (int64_t)gr * p.N + gc) = v;
+                            }
+                        }
+                    }
+        }
+        stores_behind_prologue = (OUT == OUT_BF16) && interior;
+        tm = ntm;
+        tn = ntn;
+    }
+}
+
+template <class C, int OUT>
+hipError_t launch_gemm_i8_cfg(GemmI8Args a, int num_cu, hipStream_t stream) {
+    static bool attr_set = false;
+    auto kernel = gemm_i8_dequant_kernel<C, OUT>;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    a.tiles_m = (a.M + C::BM - 1) / C::BM;
+    a.tiles_n = (a.N + C::BN - 1) / C::BN;
+    if (a.group_m <= 0) a.group_m = 8;
+    int grid = num_cu - num_cu % 8;  // a multiple of the XCD count
+    if (grid < 8) grid = 8;
+    kernel<<<grid, C::THREADS, C::LDS_BYTES, stream>>>(a);
+    return hipGetLastError();
+}
+
+}  // namespace sb
