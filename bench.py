@@ -170,7 +170,7 @@ def main():
     if not args.no_cpu_baseline:
         from oracle import switchback_oracle as oracle
         L = max(cfg.layers, key=lambda l: l.n * l.m)
-        rows = args.cpu_sample_rows or max(8, int(1.5e11 / (3.0 * L.n * L.m)))
+        rows = args.cpu_sample_rows or max(8, int(4.5e11 / (3.0 * L.n * L.m)))
         rows = min(rows, L.b)
         idx = np.linspace(0, L.b - 1, rows).astype(np.int64)
         li = cfg.layers.index(L)

@@ -27,11 +27,13 @@ namespace sb {
 
 enum { OUT_BF16 = 0, OUT_F32 = 1, OUT_I32 = 2 };
 
-template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int STAGES_, int EPI_OWN_ = 0, int NTS_ = 0, int DIAG_ = 0>
+template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int STAGES_, int EPI_OWN_ = 0, int NTS_ = 0, int DIAG_ = 0, int SPREAD_ = 0>
 struct GemmI8Cfg {
     static constexpr int EPI_OWN = EPI_OWN_;  // 1: the epilogue patch has its own LDS region, 0: it borrows the last stage
+    static constexpr int SPREAD = SPREAD_;    // 1: in-loop stage requests are issued one at a time between MFMAs
     static constexpr int NTS = NTS_;          // 1: non-temporal output stores
-    static constexpr int DIAG = DIAG_;  // 0 normal; timing diagnostics: 1 no global loads, 2 no MFMA/LDS reads, 3 all workgroups load tile (0,0)
+    static constexpr int DIAG = DIAG_;  // 0 normal; timing diagnostics (bit mask): 1 no global loads, 2 no MFMA/LDS reads, 4 no epilogue,
+                                        // 8 epilogue without its global stores, 16 conservative waits, 32 stores before the next requests
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, STAGES = STAGES_;
     static constexpr int NWAVES = WAVES_M * WAVES_N, THREADS = NWAVES * 64;
     static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;  // wave tile
@@ -55,6 +57,8 @@ struct GemmI8Cfg {
     static_assert(NWAVES * EPI_WAVE_BYTES <= STAGE_BYTES && NPRO >= 1 && (EPI_OWN || STAGES >= 3), "epilogue patch");
     static_assert(LPW * (NPRO - 1) + EPI_STORES < 64 && NPRO <= 4, "vmcnt range");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS");
+    static constexpr int LPG = LPW / KK;                          // requests per MFMA k-step group when spread
+    static_assert(!SPREAD || (EPI_OWN && LPW % KK == 0 && LPG <= MT * NT / 4 && STAGES >= 3), "spread mode");
 };
 
 struct GemmI8Args {
@@ -66,6 +70,7 @@ struct GemmI8Args {
     int M, N, K;
     int tiles_m, tiles_n;
     int group_m;  // tile rows per group of the tile walk
+    int stagger_ticks;  // start delay per XCD index in 100 MHz ticks (0 = none)
 };
 
 // Output tile visited by workgroup `wg` in its `round`-th iteration.  Workgroups are dealt to XCDs round-robin,
@@ -90,23 +95,17 @@ __device__ __forceinline__ bool gemm_tile_of(int wg, int round, int nwg, int til
 __device__ __forceinline__ void block_barrier() { asm volatile("s_barrier" ::: "memory"); }
 __device__ __forceinline__ void wait_lds_reads() { __builtin_amdgcn_s_waitcnt(0xC07F); }  // lgkmcnt(0) only
 
-// Wait until at most `later` stages (LPW loads each) plus, if `stores`, NST output stores remain outstanding.
-template <int LPW, int NST>
-__device__ __forceinline__ void wait_stage(int later, bool stores) {
-    if (stores) {
-        switch (later) {
-            case 0: wait_vmcnt<NST>(); break;
-            case 1: wait_vmcnt<LPW + NST>(); break;
-            case 2: wait_vmcnt<(2 * LPW + NST < 64 ? 2 * LPW + NST : 0)>(); break;
-            default: wait_vmcnt<(3 * LPW + NST < 64 ? 3 * LPW + NST : 0)>(); break;
-        }
-    } else {
-        switch (later) {
-            case 0: wait_vmcnt<0>(); break;
-            case 1: wait_vmcnt<LPW>(); break;
-            case 2: wait_vmcnt<(2 * LPW < 64 ? 2 * LPW : 0)>(); break;
-            default: wait_vmcnt<(3 * LPW < 64 ? 3 * LPW : 0)>(); break;
-        }
+// Wait until at most `later` stages (LPW loads each) plus EXTRA other vector-memory operations remain outstanding.
+// Counts that do not fit the 6-bit counter are clamped, which only makes the wait stricter.
+template <int LPW, int EXTRA>
+__device__ __forceinline__ void wait_stage(int later) {
+    constexpr int c0 = EXTRA < 63 ? EXTRA : 63, c1 = LPW + EXTRA < 63 ? LPW + EXTRA : 63;
+    constexpr int c2 = 2 * LPW + EXTRA < 63 ? 2 * LPW + EXTRA : 63, c3 = 3 * LPW + EXTRA < 63 ? 3 * LPW + EXTRA : 63;
+    switch (later) {
+        case 0: wait_vmcnt<c0>(); break;
+        case 1: wait_vmcnt<c1>(); break;
+        case 2: wait_vmcnt<c2>(); break;
+        default: wait_vmcnt<c3>(); break;
     }
 }
 
@@ -116,6 +115,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_i8_dequant_kernel(GemmI8Args 
     typedef __attribute__((address_space(3))) void lds_void;
     typedef const __attribute__((address_space(1))) void gbl_void;
     constexpr int S = C::STAGES;
+    constexpr int NSCALE = OUT != OUT_I32 ? C::MT : 0;  // per-lane row-scale loads per tile
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm0 = (wave / C::WAVES_N) * C::WTM, wn0 = (wave % C::WAVES_N) * C::WTN;
@@ -133,7 +133,6 @@ __global__ __launch_bounds__(C::THREADS) void gemm_i8_dequant_kernel(GemmI8Args 
 
     const int8_t *gsrc[C::LPW];
     auto set_tile_sources = [&](int tm, int tn) {
-        if (C::DIAG == 3) tm = tn = 0;
 #pragma unroll
         for (int i = 0; i < C::LPW; ++i) {
             const int srow = (wave * C::LPW + i) * C::RPS + lrow_in_slab;
@@ -149,11 +148,18 @@ __global__ __launch_bounds__(C::THREADS) void gemm_i8_dequant_kernel(GemmI8Args 
     };
     auto issue_stage = [&](int kt) {
         unsigned char *dst = smem + (kt % S) * C::STAGE_BYTES + wave * C::LPW * 1024;
-        if (C::DIAG == 1) return;
+        if (C::DIAG & 1) return;
 #pragma unroll
         for (int i = 0; i < C::LPW; ++i)
             __builtin_amdgcn_global_load_lds((gbl_void *)(gsrc[i] + (int64_t)kt * C::BK), (lds_void *)(dst + i * 1024),
                                              16, 0, 0);
+    };
+    // One request of stage kt (spread mode): request i of this wave.
+    auto issue_one = [&](int kt, int i) {
+        if (C::DIAG & 1) return;
+        unsigned char *dst = smem + (kt % S) * C::STAGE_BYTES + wave * C::LPW * 1024;
+        __builtin_amdgcn_global_load_lds((gbl_void *)(gsrc[i] + (int64_t)kt * C::BK), (lds_void *)(dst + i * 1024), 16,
+                                         0, 0);
     };
     auto issue_prologue = [&]() {
 #pragma unroll
@@ -162,8 +168,14 @@ __global__ __launch_bounds__(C::THREADS) void gemm_i8_dequant_kernel(GemmI8Args 
     };
 
     v4i xf[2][C::MT], wf[2][C::NT];
+    if (C::DIAG & 64) {  // MFMA on constant fragments (no LDS reads)
+        for (int i = 0; i < 2; ++i) {
+            for (int mt = 0; mt < C::MT; ++mt) xf[i][mt] = v4i{lane, 1, 2, 3};
+            for (int nt = 0; nt < C::NT; ++nt) wf[i][nt] = v4i{3, lane, 1, 0};
+        }
+    }
     auto read_frags = [&](int buf, int kt, int kk) {
-        if (C::DIAG == 2) return;
+        if (C::DIAG & (2 | 64)) return;
         const unsigned char *xs = smem + (kt % S) * C::STAGE_BYTES + wm0 * C::BK + frag_off[kk];
         const unsigned char *ws = smem + (kt % S) * C::STAGE_BYTES + (C::BM + wn0) * C::BK + frag_off[kk];
 #pragma unroll
@@ -171,6 +183,18 @@ __global__ __launch_bounds__(C::THREADS) void gemm_i8_dequant_kernel(GemmI8Args 
 #pragma unroll
         for (int nt = 0; nt < C::NT; ++nt) wf[buf][nt] = *reinterpret_cast<const v4i *>(ws + nt * 32 * C::BK);
     };
+
+    // Phase-shift the XCDs against each other: every tile costs the same, so without this all 256 workgroups
+    // reach their epilogue together and the output stores (an HBM-bound burst) never overlap the main loops.
+    if (p.stagger_ticks > 0) {
+        const uint64_t until = wall_clock64() + (uint64_t)((blockIdx.x & 7) * p.stagger_ticks);
+        while (wall_clock64() < until) __builtin_amdgcn_s_sleep(8);
+    }
+
+    // c = state_tensor / 127^2, read once (the pointer may alias nothing the kernel writes).
+    float tensor_scale = 0.0f;
+    if (OUT != OUT_I32) tensor_scale = p.state_tensor[0] / 16129.0f;
+    asm volatile("" : "+v"(tensor_scale));
 
     int tm, tn;
     bool have = gemm_tile_of(blockIdx.x, 0, gridDim.x, p.tiles_m, p.tiles_n, p.group_m, &tm, &tn);
@@ -193,8 +217,19 @@ __global__ __launch_bounds__(C::THREADS) void gemm_i8_dequant_kernel(GemmI8Args 
 
         // Stage 0 of this tile: behind it sit the other pre-requested stages (and the previous tile's stores).
         int issued_upto = min(C::NPRO - 1, KT - 1);
-        wait_stage<C::LPW, C::EPI_STORES>(issued_upto, stores_behind_prologue);
+        if (stores_behind_prologue)
+            wait_stage<C::LPW, C::EPI_STORES>(issued_upto);
+        else
+            wait_stage<C::LPW, 0>(issued_upto);
         block_barrier();
+        // Row absmax values of this tile, fetched now so that the epilogue finds them in registers.  They queue
+        // behind the pre-requested stages (and the previous tile's stores) and ahead of every in-loop request.
+        float srow[C::MT];
+        if (OUT != OUT_I32) {
+#pragma unroll
+            for (int mt = 0; mt < C::MT; ++mt)
+                srow[mt] = p.state_row[min(tm * C::BM + wm0 + mt * 32 + frow, p.M - 1)];
+        }
         read_frags(0, 0, 0);
 
         for (int kt = 0; kt < KT; ++kt) {
@@ -205,21 +240,39 @@ __global__ __launch_bounds__(C::THREADS) void gemm_i8_dequant_kernel(GemmI8Args 
                 } else if (kt + 1 < KT) {
                     // Hand-over: every fragment of stage kt is in (or on its way to) registers.  Retire this
                     // wave's LDS reads, make sure stage kt+1 has landed, then refill the freed stage(s).
-                    wait_stage<C::LPW, C::EPI_STORES>(issued_upto - (kt + 1), stores_behind_prologue && kt + 1 < C::NPRO);
+                    if (kt + 1 >= C::NPRO)
+                        wait_stage<C::LPW, 0>(issued_upto - (kt + 1));
+                    else if (stores_behind_prologue)
+                        wait_stage<C::LPW, C::EPI_STORES + NSCALE>(issued_upto - (kt + 1));
+                    else
+                        wait_stage<C::LPW, NSCALE>(issued_upto - (kt + 1));
                     wait_lds_reads();
                     block_barrier();
                     if (!C::EPI_OWN && kt == 0 && S - 1 < KT) issue_stage(S - 1);  // the stage the last epilogue borrowed
-                    if (kt + S < KT) issue_stage(kt + S);
+                    if (!C::SPREAD && kt + S < KT) issue_stage(kt + S);
                     issued_upto = min(KT - 1, kt + S);
                     read_frags(0, kt + 1, 0);
                 }
-                if (C::DIAG != 2) {
+                if (C::DIAG & 128) {  // LDS reads without MFMA: fold the fragments into the accumulators cheaply
+#pragma unroll
+                    for (int mt = 0; mt < C::MT; ++mt) acc[mt][0][0] ^= xf[kk & 1][mt][0] ^ wf[kk & 1][mt % C::NT][1];
+                } else if (!(C::DIAG & 2)) {
+                    // Spread mode: the stage freed by the last hand-over (k-tile kt-1+S, or kt+S once this k-tile's
+                    // own hand-over has happened) is requested piecemeal, one request after every fourth MFMA, so
+                    // that the vector-memory queue never sees a burst from all waves at once.
+                    const int spread_kt = (kk == C::KK - 1) ? kt + S : kt - 1 + S;
+                    const int spread_part = (kk == C::KK - 1) ? 0 : kk + 1;
+                    const bool spread_on = C::SPREAD && spread_kt < KT && (kk == C::KK - 1 ? kt + 1 < KT : kt >= 1);
 #pragma unroll
                     for (int mt = 0; mt < C::MT; ++mt)
 #pragma unroll
-                        for (int nt = 0; nt < C::NT; ++nt)
+                        for (int nt = 0; nt < C::NT; ++nt) {
                             acc[mt][nt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[kk & 1][nt], xf[kk & 1][mt],
                                                                                 acc[mt][nt], 0, 0, 0);
+                            const int idx = mt * C::NT + nt;
+                            if (C::SPREAD && idx % 4 == 1 && idx / 4 < C::LPG && spread_on)
+                                issue_one(spread_kt, spread_part * C::LPG + idx / 4);
+                        }
                 }
             }
         }
@@ -230,10 +283,8 @@ __global__ __launch_bounds__(C::THREADS) void gemm_i8_dequant_kernel(GemmI8Args 
         // Row scales r_i = state_row[i] * (state_tensor / 127^2), one per lane per 32-row block.
         float rscale[C::MT];
         if (OUT != OUT_I32) {
-            const float c = p.state_tensor[0] / 16129.0f;
 #pragma unroll
-            for (int mt = 0; mt < C::MT; ++mt)
-                rscale[mt] = p.state_row[min(m_base + mt * 32 + frow, p.M - 1)] * c;
+            for (int mt = 0; mt < C::MT; ++mt) rscale[mt] = srow[mt] * tensor_scale;
             // Pin the scales (and the wait for their loads) in front of the requests issued below, so that the
             // epilogue does not have to wait for the next tile's stages.
 #pragma unroll
@@ -246,7 +297,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_i8_dequant_kernel(GemmI8Args 
         block_barrier();
         int ntm, ntn;
         have = gemm_tile_of(blockIdx.x, round + 1, gridDim.x, p.tiles_m, p.tiles_n, p.group_m, &ntm, &ntn);
-        if (have) {
+        if (have && !(C::DIAG & 32)) {
             set_tile_sources(ntm, ntn);
             issue_prologue();
         }
@@ -254,7 +305,8 @@ __global__ __launch_bounds__(C::THREADS) void gemm_i8_dequant_kernel(GemmI8Args 
         __builtin_amdgcn_sched_barrier(0);
         asm volatile("" ::: "memory");
 
-        if (OUT == OUT_BF16) {
+        if (C::DIAG & 4) {
+        } else if (OUT == OUT_BF16) {
             unsigned short *out = static_cast<unsigned short *>(p.out);
             unsigned char *epi = smem + (C::EPI_OWN ? S : S - 1) * C::STAGE_BYTES + wave * C::EPI_WAVE_BYTES;
 #pragma unroll
@@ -277,7 +329,9 @@ __global__ __launch_bounds__(C::THREADS) void gemm_i8_dequant_kernel(GemmI8Args 
                     const v4u val = *reinterpret_cast<const v4u *>(epi + prow * (C::WTN * 2) +
                                                                    ((piece ^ (prow & 7)) << 4));
                     const int gr = m_base + mt * 32 + prow, gc = n_base + piece * 8;
-                    if (interior || (gr < p.M && gc < p.N)) {
+                    if (C::DIAG & 8) {
+                        if (val.x == 0x12345678u && val.y == 0x9abcdef0u) out[0] = 1;  // keep the reads alive
+                    } else if (interior || (gr < p.M && gc < p.N)) {
                         if (C::NTS)
                             __builtin_nontemporal_store(val, reinterpret_cast<v4u *>(out + (int64_t)gr * p.N + gc));
                         else
@@ -309,7 +363,11 @@ __global__ __launch_bounds__(C::THREADS) void gemm_i8_dequant_kernel(GemmI8Args 
                         }
                     }
         }
-        stores_behind_prologue = (OUT == OUT_BF16) && interior;
+        if (have && (C::DIAG & 32)) {
+            set_tile_sources(ntm, ntn);
+            issue_prologue();
+        }
+        stores_behind_prologue = (OUT == OUT_BF16) && interior && !(C::DIAG & (8 | 16 | 32));
         tm = ntm;
         tn = ntn;
     }
