@@ -25,7 +25,7 @@ hipError_t launch_gemm_i8_dequant(const int8_t *aq, const float *state_row, cons
     GemmI8Args args{aq, bq, state_row, state_tensor, out, (int)M, (int)N, (int)K, 0, 0, 8, 0};
     // 256x256 tile.  128-byte k-steps (whole cache lines per row; two LDS stages plus the epilogue patch = 160 KiB)
     // when K allows it, else 64-byte k-steps with three stages.
-    typedef GemmI8Cfg<256, 256, 128, 2, 4, 2, 1> K128;
+    typedef GemmI8Cfg<256, 256, 128, 2, 4, 2, 1, 0, 0, 2, 1> K128;  // requests spread over two k-step groups, MFMA priority
     typedef GemmI8Cfg<256, 256, 64, 2, 4, 3, 0> K64;
     const int ncu = cached_num_cu();
     const bool wide = K % 128 == 0;

@@ -27,10 +27,12 @@ namespace sb {
 
 enum { OUT_BF16 = 0, OUT_F32 = 1, OUT_I32 = 2 };
 
-template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int STAGES_, int EPI_OWN_ = 0, int NTS_ = 0, int DIAG_ = 0, int SPREAD_ = 0>
+template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int STAGES_, int EPI_OWN_ = 0, int NTS_ = 0, int DIAG_ = 0, int SPREAD_ = 0, int PRIO_ = 0>
 struct GemmI8Cfg {
     static constexpr int EPI_OWN = EPI_OWN_;  // 1: the epilogue patch has its own LDS region, 0: it borrows the last stage
-    static constexpr int SPREAD = SPREAD_;    // 1: in-loop stage requests are issued one at a time between MFMAs
+    static constexpr int SPREAD = SPREAD_;    // >0: in-loop stage requests are issued one at a time between the MFMAs of
+                                              // the first KK/SPREAD k-step groups after a stage hand-over
+    static constexpr int PRIO = PRIO_;        // 1: raise the wave priority while it issues an MFMA group
     static constexpr int NTS = NTS_;          // 1: non-temporal output stores
     static constexpr int DIAG = DIAG_;  // 0 normal; timing diagnostics (bit mask): 1 no global loads, 2 no MFMA/LDS reads, 4 no epilogue,
                                         // 8 epilogue without its global stores, 16 conservative waits, 32 stores before the next requests
@@ -57,8 +59,10 @@ struct GemmI8Cfg {
     static_assert(NWAVES * EPI_WAVE_BYTES <= STAGE_BYTES && NPRO >= 1 && (EPI_OWN || STAGES >= 3), "epilogue patch");
     static_assert(LPW * (NPRO - 1) + EPI_STORES < 64 && NPRO <= 4, "vmcnt range");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS");
-    static constexpr int LPG = LPW / KK;                          // requests per MFMA k-step group when spread
-    static_assert(!SPREAD || (EPI_OWN && LPW % KK == 0 && LPG <= MT * NT / 4 && STAGES >= 3), "spread mode");
+    static constexpr int SGROUPS = SPREAD ? KK / SPREAD : 1;        // k-step groups a stage's requests are spread over
+    static constexpr int LPG = LPW / SGROUPS;                     // requests per such group
+    static constexpr int LSTEP = MT * NT / LPG;                   // one request every LSTEP MFMAs
+    static_assert(!SPREAD || (EPI_OWN && KK % SPREAD == 0 && LPW % SGROUPS == 0 && LPG <= MT * NT), "spread mode");
 };
 
 struct GemmI8Args {
@@ -95,6 +99,34 @@ __device__ __forceinline__ bool gemm_tile_of(int wg, int round, int nwg, int til
 __device__ __forceinline__ void block_barrier() { asm volatile("s_barrier" ::: "memory"); }
 __device__ __forceinline__ void wait_lds_reads() { __builtin_amdgcn_s_waitcnt(0xC07F); }  // lgkmcnt(0) only
 
+// LDS fragment reads are written as inline asm so that the waits can be counted: the compiler's own wait insertion
+// uses lgkmcnt(0) in front of every MFMA group, which also waits for the reads just issued for the NEXT group and
+// exposes the LDS latency once per k-step.  LDS operations of a wave return in order, so "at most N outstanding"
+// means everything but the N newest has landed.  The empty asm ties each fragment register to the wait.
+template <int OFF>
+__device__ __forceinline__ v4i lds_read_b128(unsigned addr) {
+    v4i v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+    return v;
+}
+template <int STRIDE, int N, int I = 0>
+__device__ __forceinline__ void lds_read_frags(v4i (&f)[N], unsigned addr) {
+    if constexpr (I < N) {
+        f[I] = lds_read_b128<I * STRIDE>(addr);
+        lds_read_frags<STRIDE, N, I + 1>(f, addr);
+    }
+}
+template <int N>
+__device__ __forceinline__ void wait_lgkmcnt() {
+    static_assert(N >= 0 && N < 16, "lgkmcnt is a 4-bit counter");
+    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void pin_frags(v4i (&f)[N]) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) asm volatile("" : "+v"(f[i]));
+}
+
 // Wait until at most `later` stages (LPW loads each) plus EXTRA other vector-memory operations remain outstanding.
 // Counts that do not fit the 6-bit counter are clamped, which only makes the wait stricter.
 template <int LPW, int EXTRA>
@@ -117,7 +149,8 @@ __global__ __launch_bounds__(C::THREADS) void gemm_i8_dequant_kernel(GemmI8Args 
     constexpr int S = C::STAGES;
     constexpr int NSCALE = OUT != OUT_I32 ? C::MT : 0;  // per-lane row-scale loads per tile
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, so everything derived from it is scalar
     const int wm0 = (wave / C::WAVES_N) * C::WTM, wn0 = (wave % C::WAVES_N) * C::WTN;
     const int KT = p.K / C::BK;
 
@@ -133,6 +166,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_i8_dequant_kernel(GemmI8Args 
 
     const int8_t *gsrc[C::LPW];
     auto set_tile_sources = [&](int tm, int tn) {
+        if (C::DIAG & 256) { tm &= 1; tn &= 1; }  // timing diagnostic: every operand panel stays L2 resident
 #pragma unroll
         for (int i = 0; i < C::LPW; ++i) {
             const int srow = (wave * C::LPW + i) * C::RPS + lrow_in_slab;
@@ -174,14 +208,23 @@ __global__ __launch_bounds__(C::THREADS) void gemm_i8_dequant_kernel(GemmI8Args 
             for (int nt = 0; nt < C::NT; ++nt) wf[i][nt] = v4i{3, lane, 1, 0};
         }
     }
+    const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
+    static_assert((C::BM + C::BN) * C::BK <= 65536, "fragment offsets must fit the 16-bit ds offset field");
     auto read_frags = [&](int buf, int kt, int kk) {
         if (C::DIAG & (2 | 64)) return;
-        const unsigned char *xs = smem + (kt % S) * C::STAGE_BYTES + wm0 * C::BK + frag_off[kk];
-        const unsigned char *ws = smem + (kt % S) * C::STAGE_BYTES + (C::BM + wn0) * C::BK + frag_off[kk];
-#pragma unroll
-        for (int mt = 0; mt < C::MT; ++mt) xf[buf][mt] = *reinterpret_cast<const v4i *>(xs + mt * 32 * C::BK);
-#pragma unroll
-        for (int nt = 0; nt < C::NT; ++nt) wf[buf][nt] = *reinterpret_cast<const v4i *>(ws + nt * 32 * C::BK);
+        const unsigned stage = lds_base + (kt % S) * C::STAGE_BYTES + frag_off[kk];
+        lds_read_frags<32 * C::BK, C::MT>(xf[buf], stage + wm0 * C::BK);
+        lds_read_frags<32 * C::BK, C::NT>(wf[buf], stage + (C::BM + wn0) * C::BK);
+    };
+    // Fragments of buffer `buf` are safe to use once at most `newer` younger LDS reads are outstanding.
+    auto frags_ready = [&](int buf, bool newer_outstanding) {
+        if (C::DIAG & (2 | 64)) return;
+        if (newer_outstanding)
+            wait_lgkmcnt<C::MT + C::NT>();
+        else
+            wait_lgkmcnt<0>();
+        pin_frags(xf[buf]);
+        pin_frags(wf[buf]);
     };
 
     // Phase-shift the XCDs against each other: every tile costs the same, so without this all 256 workgroups
@@ -253,6 +296,9 @@ __global__ __launch_bounds__(C::THREADS) void gemm_i8_dequant_kernel(GemmI8Args 
                     issued_upto = min(KT - 1, kt + S);
                     read_frags(0, kt + 1, 0);
                 }
+                // The fragments of this k-step were requested one step earlier; the reads just issued (if any) are
+                // the only younger ones.
+                frags_ready(kk & 1, kk + 1 < C::KK || kt + 1 < KT);
                 if (C::DIAG & 128) {  // LDS reads without MFMA: fold the fragments into the accumulators cheaply
 #pragma unroll
                     for (int mt = 0; mt < C::MT; ++mt) acc[mt][0][0] ^= xf[kk & 1][mt][0] ^ wf[kk & 1][mt % C::NT][1];
@@ -262,7 +308,9 @@ __global__ __launch_bounds__(C::THREADS) void gemm_i8_dequant_kernel(GemmI8Args 
                     // that the vector-memory queue never sees a burst from all waves at once.
                     const int spread_kt = (kk == C::KK - 1) ? kt + S : kt - 1 + S;
                     const int spread_part = (kk == C::KK - 1) ? 0 : kk + 1;
-                    const bool spread_on = C::SPREAD && spread_kt < KT && (kk == C::KK - 1 ? kt + 1 < KT : kt >= 1);
+                    if (C::PRIO) __builtin_amdgcn_s_setprio(2);
+                    const bool spread_on = C::SPREAD && spread_part < C::SGROUPS && spread_kt < KT &&
+                                           (kk == C::KK - 1 ? kt + 1 < KT : kt >= 1);
 #pragma unroll
                     for (int mt = 0; mt < C::MT; ++mt)
 #pragma unroll
@@ -270,9 +318,10 @@ __global__ __launch_bounds__(C::THREADS) void gemm_i8_dequant_kernel(GemmI8Args 
                             acc[mt][nt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[kk & 1][nt], xf[kk & 1][mt],
                                                                                 acc[mt][nt], 0, 0, 0);
                             const int idx = mt * C::NT + nt;
-                            if (C::SPREAD && idx % 4 == 1 && idx / 4 < C::LPG && spread_on)
-                                issue_one(spread_kt, spread_part * C::LPG + idx / 4);
+                            if (C::SPREAD && idx % C::LSTEP == C::LSTEP - 1 && idx / C::LSTEP < C::LPG && spread_on)
+                                issue_one(spread_kt, spread_part * C::LPG + idx / C::LSTEP);
                         }
+                    if (C::PRIO) __builtin_amdgcn_s_setprio(0);
                 }
             }
         }

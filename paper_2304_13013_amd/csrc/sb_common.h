@@ -16,6 +16,7 @@ typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 typedef __bf16 v4bf __attribute__((ext_vector_type(4)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 typedef unsigned short v2us __attribute__((ext_vector_type(2)));
+typedef short v4s __attribute__((ext_vector_type(4)));
 
 // s_waitcnt that waits only on the vector-memory counter (gfx9 encoding: vmcnt = simm16[15:14]:[3:0],
 // expcnt [6:4] and lgkmcnt [11:8] left at their maxima).

@@ -13,7 +13,8 @@ bool ok_dtype(int d) { return d == SB_BF16 || d == SB_F32 || d == SB_I32_RAW; }
 int layer_shape_status(int64_t b, int64_t n, int64_t m) {
     if (b < 0 || n <= 0 || m <= 0) return SB_INVALID_ARG;
     if (n % 64 || m % 64 || b > (int64_t)1 << 30 || n > kMaxIntK || m > kMaxIntK) return SB_UNSUPPORTED_SHAPE;
-    if (b * n >= (int64_t)1 << 40 || b * m >= (int64_t)1 << 40) return SB_UNSUPPORTED_SHAPE;
+    // The weight-gradient kernel addresses dY and X through 32-bit buffer offsets (with a stage of slack).
+    if ((b + 128) * n * 2 >= (int64_t)1 << 32 || (b + 128) * m * 2 >= (int64_t)1 << 32) return SB_UNSUPPORTED_SHAPE;
     return SB_OK;
 }
 
