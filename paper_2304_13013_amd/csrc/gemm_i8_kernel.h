@@ -22,13 +22,16 @@
 //     feeds accumulators that are never stored.
 #pragma once
 #include "sb_common.h"
+#include <type_traits>
 
 namespace sb {
 
 enum { OUT_BF16 = 0, OUT_F32 = 1, OUT_I32 = 2 };
 
-template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int STAGES_, int EPI_OWN_ = 0, int NTS_ = 0, int DIAG_ = 0, int SPREAD_ = 0, int PRIO_ = 0>
+template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int STAGES_, int EPI_OWN_ = 0, int NTS_ = 0, int DIAG_ = 0, int SPREAD_ = 0, int PRIO_ = 0, int RELAX_ = 0>
 struct GemmI8Cfg {
+    static constexpr int RELAX = RELAX_;      // 1: a hand-over refills the stage finished one k-tile earlier, so it need not wait
+                                              // for this wave's LDS reads (needs STAGES >= 3 and an own epilogue patch)
     static constexpr int EPI_OWN = EPI_OWN_;  // 1: the epilogue patch has its own LDS region, 0: it borrows the last stage
     static constexpr int SPREAD = SPREAD_;    // >0: in-loop stage requests are issued one at a time between the MFMAs of
                                               // the first KK/SPREAD k-step groups after a stage hand-over
@@ -50,7 +53,9 @@ struct GemmI8Cfg {
     static constexpr int EPI_PIECES = WTN * 2 / 16;               // 16-byte pieces per row of the epilogue patch
     static constexpr int EPI_WAVE_BYTES = 32 * WTN * 2;           // 32 rows of bf16 per wave
     static constexpr int EPI_STORES = MT * (EPI_WAVE_BYTES / 1024);  // 16-byte global stores per lane per tile
-    static constexpr int NPRO = EPI_OWN ? STAGES : STAGES - 1;      // stages requested ahead of a tile's main loop
+    static constexpr int NPRO = (EPI_OWN && !RELAX) ? STAGES : STAGES - 1;  // stages requested ahead of a tile's main loop
+    static constexpr int DIST = RELAX ? STAGES - 1 : STAGES;        // hand-over of k-tile kt requests k-tile kt + DIST
+    static_assert(!RELAX || (EPI_OWN && STAGES >= 3), "relaxed hand-over");
     static constexpr int LDS_BYTES = STAGES * STAGE_BYTES + (EPI_OWN ? NWAVES * EPI_WAVE_BYTES : 0);
     static_assert(BK == 64 || BK == 128, "BK");
     static_assert(STAGES >= 2 && STAGES <= 5, "STAGES");
@@ -75,6 +80,8 @@ struct GemmI8Args {
     int tiles_m, tiles_n;
     int group_m;  // tile rows per group of the tile walk
     int stagger_ticks;  // start delay per XCD index in 100 MHz ticks (0 = none)
+    unsigned *dbg;      // DIAG 1024: timeline stamps
+    int dbg_point;      // which code point is stamped
 };
 
 // Output tile visited by workgroup `wg` in its `round`-th iteration.  Workgroups are dealt to XCDs round-robin,
@@ -201,8 +208,14 @@ __global__ __launch_bounds__(C::THREADS) void gemm_i8_dequant_kernel(GemmI8Args 
             if (s < KT) issue_stage(s);
     };
 
+    // MFMA operand fragments, double-buffered in registers.  A k-step group issues its MFMAs in the order
+    // (x0,w0) (x0,w1) (x1,w0) (x1,w1) ... and reads the NEXT group's fragments in the order w0 x0 w1 x1 x2 x3, one
+    // read after each of its first six MFMAs: an LDS read issued in the shadow of an MFMA costs no issue time,
+    // whereas six reads in a row from all eight waves at once stall every wave until the LDS has accepted them.
+    static_assert(C::MT == 4 && C::NT == 2, "fragment schedule below is written for 4x2 MFMA blocks per wave");
+    constexpr int NFRAG = C::MT + C::NT;
     v4i xf[2][C::MT], wf[2][C::NT];
-    if (C::DIAG & 64) {  // MFMA on constant fragments (no LDS reads)
+    if (C::DIAG & 64) {  // timing diagnostic: MFMA on constant fragments (no LDS reads)
         for (int i = 0; i < 2; ++i) {
             for (int mt = 0; mt < C::MT; ++mt) xf[i][mt] = v4i{lane, 1, 2, 3};
             for (int nt = 0; nt < C::NT; ++nt) wf[i][nt] = v4i{3, lane, 1, 0};
@@ -210,21 +223,42 @@ __global__ __launch_bounds__(C::THREADS) void gemm_i8_dequant_kernel(GemmI8Args 
     }
     const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
     static_assert((C::BM + C::BN) * C::BK <= 65536, "fragment offsets must fit the 16-bit ds offset field");
-    auto read_frags = [&](int buf, int kt, int kk) {
-        if (C::DIAG & (2 | 64)) return;
-        const unsigned stage = lds_base + (kt % S) * C::STAGE_BYTES + frag_off[kk];
-        lds_read_frags<32 * C::BK, C::MT>(xf[buf], stage + wm0 * C::BK);
-        lds_read_frags<32 * C::BK, C::NT>(wf[buf], stage + (C::BM + wn0) * C::BK);
+    const unsigned x_off = wm0 * C::BK, w_off = (C::BM + wn0) * C::BK;
+    // i-th fragment read of the group (k-tile kt, k-step kk) into register buffer buf.
+    auto issue_frag_read = [&](int i, int buf, int kt, int kk) {
+        if (C::DIAG & 64) return;
+        const unsigned at = lds_base + (kt % S) * C::STAGE_BYTES + frag_off[kk];
+        switch (i) {
+            case 0: wf[buf][0] = lds_read_b128<0>(at + w_off); break;
+            case 1: xf[buf][0] = lds_read_b128<0>(at + x_off); break;
+            case 2: wf[buf][1] = lds_read_b128<32 * C::BK>(at + w_off); break;
+            case 3: xf[buf][1] = lds_read_b128<32 * C::BK>(at + x_off); break;
+            case 4: xf[buf][2] = lds_read_b128<64 * C::BK>(at + x_off); break;
+            default: xf[buf][3] = lds_read_b128<96 * C::BK>(at + x_off); break;
+        }
     };
-    // Fragments of buffer `buf` are safe to use once at most `newer` younger LDS reads are outstanding.
-    auto frags_ready = [&](int buf, bool newer_outstanding) {
-        if (C::DIAG & (2 | 64)) return;
-        if (newer_outstanding)
-            wait_lgkmcnt<C::MT + C::NT>();
-        else
-            wait_lgkmcnt<0>();
-        pin_frags(xf[buf]);
-        pin_frags(wf[buf]);
+    // Ties the register of the i-th fragment read to the wait that precedes this call.
+    auto pin_frag = [&](int i, int buf) {
+        switch (i) {
+            case 0: asm volatile("" : "+v"(wf[buf][0])); break;
+            case 1: asm volatile("" : "+v"(xf[buf][0])); break;
+            case 2: asm volatile("" : "+v"(wf[buf][1])); break;
+            case 3: asm volatile("" : "+v"(xf[buf][1])); break;
+            case 4: asm volatile("" : "+v"(xf[buf][2])); break;
+            default: asm volatile("" : "+v"(xf[buf][3])); break;
+        }
+    };
+    auto wait_lgkm_at_most = [&](int n) {
+        if (C::DIAG & 64) return;
+        switch (n) {
+            case 0: wait_lgkmcnt<0>(); break;
+            case 1: wait_lgkmcnt<1>(); break;
+            case 2: wait_lgkmcnt<2>(); break;
+            case 3: wait_lgkmcnt<3>(); break;
+            case 4: wait_lgkmcnt<4>(); break;
+            case 5: wait_lgkmcnt<5>(); break;
+            default: wait_lgkmcnt<6>(); break;
+        }
     };
 
     // Phase-shift the XCDs against each other: every tile costs the same, so without this all 256 workgroups
@@ -249,7 +283,14 @@ __global__ __launch_bounds__(C::THREADS) void gemm_i8_dequant_kernel(GemmI8Args 
     // the vector-memory queue (false when unknown, which only makes the waits stricter).
     bool stores_behind_prologue = false;
 
+    unsigned dbg_epi_end = 0, dbg_prologue_issued = 0;
     for (int round = 0; have; ++round) {
+        auto stamp = [&](int idx) {
+            if ((C::DIAG & 1024) && round < 2) {
+                const unsigned t = (unsigned)__builtin_readcyclecounter();
+                if (lane == 0) *reinterpret_cast<unsigned *>(smem + S * C::STAGE_BYTES + wave * C::EPI_WAVE_BYTES + idx * 4) = t;
+            }
+        };
         v16i acc[C::MT][C::NT];
 #pragma unroll
         for (int mt = 0; mt < C::MT; ++mt)
@@ -265,6 +306,9 @@ __global__ __launch_bounds__(C::THREADS) void gemm_i8_dequant_kernel(GemmI8Args 
         else
             wait_stage<C::LPW, 0>(issued_upto);
         block_barrier();
+        stamp(200);
+        if ((C::DIAG & 1024) && round < 2 && lane == 0)
+            *reinterpret_cast<unsigned *>(smem + S * C::STAGE_BYTES + wave * C::EPI_WAVE_BYTES + 202 * 4) = (unsigned)wall_clock64();
         // Row absmax values of this tile, fetched now so that the epilogue finds them in registers.  They queue
         // behind the pre-requested stages (and the previous tile's stores) and ahead of every in-loop request.
         float srow[C::MT];
@@ -273,59 +317,89 @@ __global__ __launch_bounds__(C::THREADS) void gemm_i8_dequant_kernel(GemmI8Args 
             for (int mt = 0; mt < C::MT; ++mt)
                 srow[mt] = p.state_row[min(tm * C::BM + wm0 + mt * 32 + frow, p.M - 1)];
         }
-        read_frags(0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < NFRAG; ++i) issue_frag_read(i, 0, 0, 0);
 
-        for (int kt = 0; kt < KT; ++kt) {
+        // One k-tile (stage).  The tile's last k-tile is a separate instantiation, so that "another k-step group
+        // follows" is known at compile time and the hot loop carries no branches for it.
+        auto k_tile = [&](const int kt, auto is_last_tile) {
+            constexpr bool last_tile = decltype(is_last_tile)::value;
 #pragma unroll
             for (int kk = 0; kk < C::KK; ++kk) {
-                if (kk + 1 < C::KK) {
-                    read_frags((kk + 1) & 1, kt, kk + 1);
-                } else if (kt + 1 < KT) {
-                    // Hand-over: every fragment of stage kt is in (or on its way to) registers.  Retire this
-                    // wave's LDS reads, make sure stage kt+1 has landed, then refill the freed stage(s).
+                const bool last_group = kk + 1 == C::KK;
+                const bool has_next = !last_group || !last_tile;   // another k-step group follows in this tile
+                const bool handed_over = last_group && has_next;
+                if (handed_over) {
+                    // Hand-over: the fragments of this last k-step of stage kt are in (or on their way to)
+                    // registers.  Retire this wave's LDS reads, make sure stage kt+1 has landed, then let the
+                    // freed stage be refilled.
+                    if (p.dbg_point == 12) stamp(kt * 4 + 0);
                     if (kt + 1 >= C::NPRO)
                         wait_stage<C::LPW, 0>(issued_upto - (kt + 1));
                     else if (stores_behind_prologue)
                         wait_stage<C::LPW, C::EPI_STORES + NSCALE>(issued_upto - (kt + 1));
                     else
                         wait_stage<C::LPW, NSCALE>(issued_upto - (kt + 1));
-                    wait_lds_reads();
+                    if (p.dbg_point == 13) stamp(kt * 4 + 0);
+                    if (!C::RELAX) wait_lds_reads();
+                    if (p.dbg_point == 14) stamp(kt * 4 + 0);
                     block_barrier();
+                    stamp(kt * 4 + 3);
                     if (!C::EPI_OWN && kt == 0 && S - 1 < KT) issue_stage(S - 1);  // the stage the last epilogue borrowed
-                    if (!C::SPREAD && kt + S < KT) issue_stage(kt + S);
-                    issued_upto = min(KT - 1, kt + S);
-                    read_frags(0, kt + 1, 0);
+                    if (!C::SPREAD && kt + C::DIST < KT) issue_stage(kt + C::DIST);
+                    issued_upto = min(KT - 1, kt + C::DIST);
                 }
-                // The fragments of this k-step were requested one step earlier; the reads just issued (if any) are
-                // the only younger ones.
-                frags_ready(kk & 1, kk + 1 < C::KK || kt + 1 < KT);
-                if (C::DIAG & 128) {  // LDS reads without MFMA: fold the fragments into the accumulators cheaply
+                // Spread mode: the stage freed by the last hand-over (k-tile kt-1+S, or kt+S once this k-tile's own
+                // hand-over has happened) is requested piecemeal between the MFMAs, so that the vector-memory
+                // queue never sees a burst from all waves at once.
+                const int spread_kt = last_group ? kt + C::DIST : kt - 1 + C::DIST;
+                const int spread_part = last_group ? 0 : kk + 1;
+                const bool spread_on = C::SPREAD && spread_part < C::SGROUPS && spread_kt < KT &&
+                                       (last_group ? !last_tile : kt >= 1);
+                const int cur = kk & 1, nxt = (kk + 1) & 1;
+                const int next_kt = last_group ? kt + 1 : kt, next_kk = last_group ? 0 : kk + 1;
+                if (p.dbg_point == kk * 3 + 0) stamp(kt * 4 + 0);
+                if (C::PRIO) __builtin_amdgcn_s_setprio(2);
+                int landed = 0;  // fragments of this group known to have landed
 #pragma unroll
-                    for (int mt = 0; mt < C::MT; ++mt) acc[mt][0][0] ^= xf[kk & 1][mt][0] ^ wf[kk & 1][mt % C::NT][1];
-                } else if (!(C::DIAG & 2)) {
-                    // Spread mode: the stage freed by the last hand-over (k-tile kt-1+S, or kt+S once this k-tile's
-                    // own hand-over has happened) is requested piecemeal, one request after every fourth MFMA, so
-                    // that the vector-memory queue never sees a burst from all waves at once.
-                    const int spread_kt = (kk == C::KK - 1) ? kt + S : kt - 1 + S;
-                    const int spread_part = (kk == C::KK - 1) ? 0 : kk + 1;
-                    if (C::PRIO) __builtin_amdgcn_s_setprio(2);
-                    const bool spread_on = C::SPREAD && spread_part < C::SGROUPS && spread_kt < KT &&
-                                           (kk == C::KK - 1 ? kt + 1 < KT : kt >= 1);
+                for (int idx = 0; idx < C::MT * C::NT; ++idx) {
+                    const int mt = idx / C::NT, nt = idx % C::NT;
+                    // Reads of this group that MFMA idx needs: w0 x0 | w1 | x1 | - | x2 | - | x3 | -
+                    const int need = idx == 0 ? 2 : idx == 1 ? 3 : idx < 4 ? 4 : idx < 6 ? 5 : 6;
+                    if (need > landed) {
+                        // LDS reads return in order: all but the (NFRAG - need) youngest of this group's reads, and
+                        // the reads already issued for the next group, must be back.
+                        if (!has_next)
+                            wait_lgkm_at_most(NFRAG - need);
+                        else if (!handed_over || C::RELAX)
+                            wait_lgkm_at_most(NFRAG - need + min(idx, NFRAG));
+                        // (a hand-over that waits for all LDS reads leaves nothing to wait for)
 #pragma unroll
-                    for (int mt = 0; mt < C::MT; ++mt)
-#pragma unroll
-                        for (int nt = 0; nt < C::NT; ++nt) {
-                            acc[mt][nt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[kk & 1][nt], xf[kk & 1][mt],
-                                                                                acc[mt][nt], 0, 0, 0);
-                            const int idx = mt * C::NT + nt;
-                            if (C::SPREAD && idx % C::LSTEP == C::LSTEP - 1 && idx / C::LSTEP < C::LPG && spread_on)
-                                issue_one(spread_kt, spread_part * C::LPG + idx / C::LSTEP);
-                        }
-                    if (C::PRIO) __builtin_amdgcn_s_setprio(0);
+                        for (int i = landed; i < need; ++i) pin_frag(i, cur);
+                        landed = need;
+                    }
+                    if (idx == 1 && p.dbg_point == kk * 3 + 1) stamp(kt * 4 + 0);
+                    acc[mt][nt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[cur][nt], xf[cur][mt], acc[mt][nt], 0, 0, 0);
+                    if (idx < NFRAG && has_next) issue_frag_read(idx, nxt, next_kt, next_kk);
+                    if (C::SPREAD && idx % C::LSTEP == C::LSTEP - 1 && idx / C::LSTEP < C::LPG && spread_on)
+                        issue_one(spread_kt, spread_part * C::LPG + idx / C::LSTEP);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
+                if (C::PRIO) __builtin_amdgcn_s_setprio(0);
+                if (p.dbg_point == kk * 3 + 2) stamp(kt * 4 + 0);
             }
-        }
+        };
+        for (int kt = 0; kt + 1 < KT; ++kt) k_tile(kt, std::false_type());
+        k_tile(KT - 1, std::true_type());
 
+        stamp(201);
+        if ((C::DIAG & 1024) && round < 2 && lane == 0)
+            *reinterpret_cast<unsigned *>(smem + S * C::STAGE_BYTES + wave * C::EPI_WAVE_BYTES + 203 * 4) = (unsigned)wall_clock64();
+        if ((C::DIAG & 1024) && round < 2 && p.dbg && lane < 52 && (blockIdx.x == 0 || blockIdx.x == 37)) {
+            const unsigned *src = reinterpret_cast<const unsigned *>(smem + S * C::STAGE_BYTES + wave * C::EPI_WAVE_BYTES);
+            unsigned *dst = p.dbg + (((blockIdx.x ? 1 : 0) * 8 + wave) * 2 + round) * 208;
+            for (int i = lane; i < 208; i += 52) dst[i] = i == 204 ? dbg_epi_end : i == 205 ? dbg_prologue_issued : src[i];
+        }
         const int m_base = tm * C::BM + wm0, n_base = tn * C::BN + wn0;
         const bool interior = (tm + 1) * C::BM <= p.M && (tn + 1) * C::BN <= p.N;
 
@@ -350,6 +424,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_i8_dequant_kernel(GemmI8Args 
             set_tile_sources(ntm, ntn);
             issue_prologue();
         }
+        if (C::DIAG & 1024) dbg_prologue_issued = (unsigned)__builtin_readcyclecounter();
         // The wait counts of the next main loop assume these requests precede the output stores below.
         __builtin_amdgcn_sched_barrier(0);
         asm volatile("" ::: "memory");
@@ -416,6 +491,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_i8_dequant_kernel(GemmI8Args 
             set_tile_sources(ntm, ntn);
             issue_prologue();
         }
+        if (C::DIAG & 1024) dbg_epi_end = (unsigned)__builtin_readcyclecounter();
         stores_behind_prologue = (OUT == OUT_BF16) && interior && !(C::DIAG & (8 | 16 | 32));
         tm = ntm;
         tn = ntn;
