@@ -4,7 +4,7 @@
 namespace sb {
 namespace {
 
-typedef GemmBf16Cfg<2, 2, 1> Cfg;
+typedef GemmBf16Cfg<2, 4> Cfg;
 constexpr int MAX_SPLITS = 16;
 
 __global__ __launch_bounds__(Cfg::THREADS) void gemm_bf16_tn_kernel(GemmBf16Args p) { gemm_bf16_tn_body<Cfg>(p); }

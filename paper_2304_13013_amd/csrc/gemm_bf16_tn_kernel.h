@@ -9,8 +9,9 @@
 // i/4+8 and i/4+12, so with lane r addressing token r/4 and columns 4*(r%4).. a lane receives one column at four
 // consecutive tokens; two such reads make the 8-token operand of v_mfma_f32_32x32x16_bf16.
 //
-// Pipeline, tile walk and barriers are those of the int8 kernel (gemm_i8_kernel.h): 256x256 tile, 8 waves with
-// 128x64 wave tiles, two LDS stages of 64 tokens, requests issued between MFMAs, bare s_barrier with counted waits.
+// Pipeline, wave roles and barriers are those of the int8 kernel (gemm_i8_kernel.h): 256x256 tile, 8 waves with
+// 128x64 wave tiles, two LDS stages of 64 tokens, four loader waves, fragment reads issued between the MFMAs of
+// the preceding k-step, bare s_barrier with counted waits.
 // The X-side tile is the MFMA's first operand and the dY-side tile its second, so a lane owns one dW row.
 //
 // The contraction is long (b ~ 32k) and the output small, so work items are (split, tile) pairs (split-K); they are
@@ -30,23 +31,26 @@ struct GemmBf16Args {
     int b, n, m;
     int tiles_m, tiles_n, splits, k_per_split;  // k_per_split is a multiple of the stage length
     int out_bf16;
+#ifdef SB_GEMM_TIMELINE
+    unsigned *dbg;
+    int dbg_point;
+#endif
 };
 
-template <int STAGES_ = 2, int SPREAD_ = 2, int PRIO_ = 1>
+template <int STAGES_ = 2, int LOADERS_ = 4>
 struct GemmBf16Cfg {
     static constexpr int BM = 256, BN = 256, BKT = 64;  // dW rows (dY columns), dW columns (X columns), tokens/stage
-    static constexpr int STAGES = STAGES_, SPREAD = SPREAD_, PRIO = PRIO_;
+    static constexpr int STAGES = STAGES_, LOADERS = LOADERS_;
     static constexpr int WAVES_M = 2, WAVES_N = 4, NWAVES = 8, THREADS = 512;
     static constexpr int WTM = 128, WTN = 64, MT = 4, NT = 2;
     static constexpr int KK = BKT / 16;                       // MFMA k-steps (16 tokens) per stage
     static constexpr int OP_BYTES = BKT * 512;                // one operand tile: BKT token rows of 256 bf16
     static constexpr int STAGE_BYTES = 2 * OP_BYTES;          // dY tile then X tile
-    static constexpr int LPW = STAGE_BYTES / 1024 / NWAVES;   // 1 KiB requests (two token rows of one operand) per wave
-    static constexpr int SGROUPS = SPREAD ? KK / SPREAD : 1;
-    static constexpr int LPG = LPW / SGROUPS, LSTEP = MT * NT / LPG;
+    static constexpr int LPW = STAGE_BYTES / 1024 / LOADERS;  // 1 KiB requests (two token rows of one operand) per loader wave
     static constexpr int EPI_WAVE_BYTES = 32 * WTN * 2, EPI_PIECES = WTN * 2 / 16;
     static constexpr int LDS_BYTES = STAGES * STAGE_BYTES + NWAVES * EPI_WAVE_BYTES;
-    static_assert(STAGES >= 2 && LDS_BYTES <= 160 * 1024 && LPW % SGROUPS == 0 && LPG <= MT * NT, "configuration");
+    static_assert(STAGES >= 2 && LDS_BYTES <= 160 * 1024 && (LOADERS == 4 || LOADERS == 8), "configuration");
+    static_assert(LPW * (STAGES - 1) < 64, "vmcnt range");
 };
 
 // The kernel body; the __global__ entry that calls it lives next to the launcher (a __global__ template that uses
@@ -55,7 +59,6 @@ template <class C>
 __device__ __forceinline__ void gemm_bf16_tn_body(const GemmBf16Args &p) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     typedef __attribute__((address_space(3))) void lds_void;
-    typedef __attribute__((address_space(3))) v4s lds_v4s;
     constexpr int S = C::STAGES;
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -63,47 +66,37 @@ __device__ __forceinline__ void gemm_bf16_tn_body(const GemmBf16Args &p) {
     const int wm0 = (wave / C::WAVES_N) * C::WTM, wn0 = (wave % C::WAVES_N) * C::WTN;
     const int frow = lane & 31, fhalf = lane >> 5;
 
-    // Buffer resources: the bounds check (num_records in bytes) turns token rows past b into zeros.
-    const __amdgpu_buffer_rsrc_t rsrc_dy =
-        __builtin_amdgcn_make_buffer_rsrc((void *)p.dy, 0, (unsigned)((size_t)p.b * p.m * 2), 0x00020000);
-    const __amdgpu_buffer_rsrc_t rsrc_x =
-        __builtin_amdgcn_make_buffer_rsrc((void *)p.x, 0, (unsigned)((size_t)p.b * p.n * 2), 0x00020000);
-
-    // Loader role.  Request i of wave w fills 1 KiB = token rows (2j, 2j+1) of one operand tile, j = (w*LPW+i) % 32;
-    // requests with w*LPW+i < 32 load dY, the rest X.  LDS slot (token, p) holds 16-byte column chunk
-    // p ^ ((token & 3) << 2): token rows are 512 bytes apart, so without it the four token rows one transposing read
-    // touches would all fall into the same 64-byte bank window.
+    // Loader role (see the int8 kernel for why only LOADERS waves issue requests, all right after a hand-over).
+    // Request i of loader wave w fills 1 KiB = token rows (2j, 2j+1) of one operand tile, j = (w*LPW + i) % 32; the
+    // first 32 requests of a stage load dY, the rest X, so a wave loads one operand only.  LDS slot (token, p) holds
+    // 16-byte column chunk p ^ ((token & 3) << 2): token rows are 512 bytes apart, so without it the four token rows
+    // one transposing read touches would all fall into the same 64-byte bank window.  A lane's byte offset is
+    //   voff[i & 1] (per lane: its token of the pair, its swizzled chunk) + i * 4 * ld + item_soff + kt * BKT * 2 * ld.
+    // Columns past the operand's width (partial tiles) read the next token row or, at the very end, zeros from the
+    // bounds check; they only feed results that are never stored.
+    const bool loader = wave < C::LOADERS;
+    const bool loads_dy = wave * C::LPW < 32;
+    const unsigned ld = loads_dy ? p.m : p.n;  // row length of the operand this wave loads
+    // The bounds check of the buffer resource (num_records in bytes) turns token rows past b into zeros.
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)(loads_dy ? p.dy : p.x), 0, (unsigned)((size_t)p.b * ld * 2), 0x00020000);
     const int l_tok = lane >> 5, l_pos = lane & 31;
-    unsigned voff[C::LPW];          // byte offset of this lane's 16 bytes for stage 0 of the current work item
-    unsigned vstep_dy, vstep_x;     // bytes per stage
-    vstep_dy = (unsigned)C::BKT * p.m * 2;
-    vstep_x = (unsigned)C::BKT * p.n * 2;
-    auto set_item_sources = [&](int tm, int tn, int k_begin) {
+    const int tok0 = ((wave * C::LPW) % 32) * 2;  // first token row of the wave's share within a stage
+    unsigned voff[2];
 #pragma unroll
-        for (int i = 0; i < C::LPW; ++i) {
-            const int req = wave * C::LPW + i;
-            const int tok = (req & 31) * 2 + l_tok;
-            const int chunk = l_pos ^ ((tok & 3) << 2);
-            if (req < 32) {
-                const int col = min(tm * C::BM + chunk * 8, p.m - 8);
-                voff[i] = ((unsigned)(k_begin + tok) * p.m + col) * 2;
-            } else {
-                const int col = min(tn * C::BN + chunk * 8, p.n - 8);
-                voff[i] = ((unsigned)(k_begin + tok) * p.n + col) * 2;
-            }
-        }
-    };
-    auto issue_one = [&](int kt, int i) {
-        const int req = wave * C::LPW + i;
-        unsigned char *dst = smem + (kt % S) * C::STAGE_BYTES + req * 1024;
-        if (req < 32)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_dy, (lds_void *)dst, 16, voff[i] + kt * vstep_dy, 0, 0, 0);
-        else
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_x, (lds_void *)dst, 16, voff[i] + kt * vstep_x, 0, 0, 0);
+    for (int v = 0; v < 2; ++v) voff[v] = ((unsigned)l_tok * ld + ((l_pos ^ ((2 * v + l_tok) << 2)) << 3)) * 2;
+    const unsigned req_step = 4 * ld, stage_step = (unsigned)C::BKT * 2 * ld;
+    unsigned item_soff = 0;
+    auto set_item_sources = [&](int tm, int tn, int k_begin) {
+        item_soff = ((unsigned)(k_begin + tok0) * ld + (unsigned)(loads_dy ? tm * C::BM : tn * C::BN)) * 2;
     };
     auto issue_stage = [&](int kt) {
+        unsigned char *dst = smem + (kt % S) * C::STAGE_BYTES + wave * C::LPW * 1024;
+        const unsigned soff = item_soff + (unsigned)kt * stage_step;
 #pragma unroll
-        for (int i = 0; i < C::LPW; ++i) issue_one(kt, i);
+        for (int i = 0; i < C::LPW; ++i)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)(dst + i * 1024), 16, voff[i & 1],
+                                                     soff + (unsigned)i * req_step, 0, 0);
     };
 
     // Fragment reads.  Lane l: 16-lane group g = l/16 covers columns 16*(g%2).. of the 32-column block and token
@@ -134,22 +127,43 @@ __device__ __forceinline__ void gemm_bf16_tn_body(const GemmBf16Args &p) {
         asm volatile("ds_read_b64_tr_b16 %0, %1 offset:2048" : "=v"(hi) : "v"(addr));
         return __builtin_bit_cast(v8bf, __builtin_shufflevector(lo, hi, 0, 1, 2, 3));
     };
-    auto read_frags = [&](int buf, int kt, int kk) {
+    // Fragment schedule of the int8 kernel: a k-step group issues its MFMAs in the order (g0,x0) (g0,x1) (g1,x0) ...
+    // and reads the next group's fragments in the order x0 g0 x1 g1 g2 g3, one fragment (two transposing reads) after
+    // each of its first six MFMAs.
+    static_assert(C::MT == 4 && C::NT == 2, "fragment schedule below is written for 4x2 MFMA blocks per wave");
+    constexpr int NFRAG = C::MT + C::NT;
+    auto issue_frag_read = [&](int i, int buf, int kt, int kk) {
         const unsigned base = lds_base + (kt % S) * C::STAGE_BYTES + kk * (16 * 512);
-#pragma unroll
-        for (int mt = 0; mt < C::MT; ++mt) gf[buf][mt] = read_pair(base + goff[mt]);
-#pragma unroll
-        for (int nt = 0; nt < C::NT; ++nt) xf[buf][nt] = read_pair(base + xoff[nt]);
+        switch (i) {
+            case 0: xf[buf][0] = read_pair(base + xoff[0]); break;
+            case 1: gf[buf][0] = read_pair(base + goff[0]); break;
+            case 2: xf[buf][1] = read_pair(base + xoff[1]); break;
+            case 3: gf[buf][1] = read_pair(base + goff[1]); break;
+            case 4: gf[buf][2] = read_pair(base + goff[2]); break;
+            default: gf[buf][3] = read_pair(base + goff[3]); break;
+        }
     };
-    auto frags_ready = [&](int buf, bool newer_outstanding) {
-        if (newer_outstanding)
-            wait_lgkmcnt<2 * (C::MT + C::NT)>();
-        else
-            wait_lgkmcnt<0>();
-#pragma unroll
-        for (int mt = 0; mt < C::MT; ++mt) asm volatile("" : "+v"(gf[buf][mt]));
-#pragma unroll
-        for (int nt = 0; nt < C::NT; ++nt) asm volatile("" : "+v"(xf[buf][nt]));
+    auto pin_frag = [&](int i, int buf) {
+        switch (i) {
+            case 0: asm volatile("" : "+v"(xf[buf][0])); break;
+            case 1: asm volatile("" : "+v"(gf[buf][0])); break;
+            case 2: asm volatile("" : "+v"(xf[buf][1])); break;
+            case 3: asm volatile("" : "+v"(gf[buf][1])); break;
+            case 4: asm volatile("" : "+v"(gf[buf][2])); break;
+            default: asm volatile("" : "+v"(gf[buf][3])); break;
+        }
+    };
+    // At most n fragment reads (two LDS reads each) outstanding.
+    auto wait_frags_at_most = [&](int n) {
+        switch (n) {
+            case 0: wait_lgkmcnt<0>(); break;
+            case 1: wait_lgkmcnt<2>(); break;
+            case 2: wait_lgkmcnt<4>(); break;
+            case 3: wait_lgkmcnt<6>(); break;
+            case 4: wait_lgkmcnt<8>(); break;
+            case 5: wait_lgkmcnt<10>(); break;
+            default: wait_lgkmcnt<12>(); break;
+        }
     };
 
     // Work items: XCD x (workgroup id % 8) owns the contiguous run [x*per_xcd, (x+1)*per_xcd) of split-major items.
@@ -176,12 +190,23 @@ __device__ __forceinline__ void gemm_bf16_tn_body(const GemmBf16Args &p) {
     if (have) {
         KT = stages_of(split);
         set_item_sources(tm, tn, split * p.k_per_split);
+        if (loader) {
 #pragma unroll
-        for (int s = 0; s < S; ++s)
-            if (s < KT) issue_stage(s);
+            for (int s = 0; s < S; ++s)
+                if (s < KT) issue_stage(s);
+        }
     }
 
     for (int round = 0; have; ++round) {
+#ifdef SB_GEMM_TIMELINE
+        auto stamp = [&](int idx) {
+            if (round < 2) {
+                const unsigned t = (unsigned)__builtin_readcyclecounter();
+                if (lane == 0)
+                    *reinterpret_cast<unsigned *>(smem + S * C::STAGE_BYTES + wave * C::EPI_WAVE_BYTES + idx * 4) = t;
+            }
+        };
+#endif
         v16f acc[C::MT][C::NT];
 #pragma unroll
         for (int mt = 0; mt < C::MT; ++mt)
@@ -193,44 +218,68 @@ __device__ __forceinline__ void gemm_bf16_tn_body(const GemmBf16Args &p) {
         // Unlike the int8 kernel the epilogue stores here are few (the output is small), so the waits simply
         // count requests and treat everything older as retired in order.
         int issued_upto = min(S - 1, KT - 1);
-        if (KT > 0) {
-            wait_stage<C::LPW, 0>(issued_upto);
-            block_barrier();
-            read_frags(0, 0, 0);
-        }
-        for (int kt = 0; kt < KT; ++kt) {
+        auto k_tile = [&](const int kt, auto is_last_tile) {
+            constexpr bool last_tile = decltype(is_last_tile)::value;
 #pragma unroll
             for (int kk = 0; kk < C::KK; ++kk) {
-                if (kk + 1 < C::KK) {
-                    read_frags((kk + 1) & 1, kt, kk + 1);
-                } else if (kt + 1 < KT) {
-                    wait_stage<C::LPW, 0>(issued_upto - (kt + 1));
+                const bool last_group = kk + 1 == C::KK;
+                const bool has_next = !last_group || !last_tile;  // another k-step group follows in this item
+                const bool handed_over = last_group && has_next;
+                if (handed_over) {
+                    // Stage hand-over (see the int8 kernel): this wave's reads of stage kt are retired, stage kt+1
+                    // has landed, the freed stage may be refilled.
+                    if (kt < 50) SB_STAMP_AT(12, kt * 4 + 0);
+                    if (loader) wait_stage<C::LPW, 0>(issued_upto - (kt + 1));
+                    if (kt < 50) SB_STAMP_AT(13, kt * 4 + 0);
                     wait_lds_reads();
+                    if (kt < 50) SB_STAMP_AT(14, kt * 4 + 0);
                     block_barrier();
-                    if (!C::SPREAD && kt + S < KT) issue_stage(kt + S);
+                    if (kt < 50) SB_STAMP(kt * 4 + 3);
+                    if (loader && kt + S < KT) issue_stage(kt + S);
                     issued_upto = min(KT - 1, kt + S);
-                    read_frags(0, kt + 1, 0);
                 }
-                frags_ready(kk & 1, kk + 1 < C::KK || kt + 1 < KT);
-                if (C::PRIO) __builtin_amdgcn_s_setprio(2);
-                const int spread_kt = (kk == C::KK - 1) ? kt + S : kt - 1 + S;
-                const int spread_part = (kk == C::KK - 1) ? 0 : kk + 1;
-                const bool spread_on = C::SPREAD && spread_part < C::SGROUPS && spread_kt < KT &&
-                                       (kk == C::KK - 1 ? kt + 1 < KT : kt >= 1);
+                const int cur = kk & 1, nxt = (kk + 1) & 1;
+                const int next_kt = last_group ? kt + 1 : kt, next_kk = last_group ? 0 : kk + 1;
+                int landed = 0;
+                if (kt < 50) SB_STAMP_AT(kk * 3 + 0, kt * 4 + 0);
 #pragma unroll
-                for (int mt = 0; mt < C::MT; ++mt)
+                for (int idx = 0; idx < C::MT * C::NT; ++idx) {
+                    const int mt = idx / C::NT, nt = idx % C::NT;
+                    const int need = idx == 0 ? 2 : idx == 1 ? 3 : idx < 4 ? 4 : idx < 6 ? 5 : 6;
+                    if (idx == 1 && kt < 50) SB_STAMP_AT(kk * 3 + 1, kt * 4 + 0);
+                    if (need > landed) {
+                        if (!has_next)
+                            wait_frags_at_most(NFRAG - need);
+                        else if (!handed_over)
+                            wait_frags_at_most(NFRAG - need + min(idx, NFRAG));
 #pragma unroll
-                    for (int nt = 0; nt < C::NT; ++nt) {
-                        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf[kk & 1][nt], gf[kk & 1][mt],
-                                                                              acc[mt][nt], 0, 0, 0);
-                        const int idx = mt * C::NT + nt;
-                        if (C::SPREAD && idx % C::LSTEP == C::LSTEP - 1 && idx / C::LSTEP < C::LPG && spread_on)
-                            issue_one(spread_kt, spread_part * C::LPG + idx / C::LSTEP);
+                        for (int i = landed; i < need; ++i) pin_frag(i, cur);
+                        landed = need;
                     }
-                if (C::PRIO) __builtin_amdgcn_s_setprio(0);
+                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf[cur][nt], gf[cur][mt], acc[mt][nt], 0, 0, 0);
+                    if (idx < NFRAG && has_next) issue_frag_read(idx, nxt, next_kt, next_kk);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                if (kt < 50) SB_STAMP_AT(kk * 3 + 2, kt * 4 + 0);
             }
+        };
+        if (KT > 0) {
+            if (loader) wait_stage<C::LPW, 0>(issued_upto);
+            block_barrier();
+#pragma unroll
+            for (int i = 0; i < NFRAG; ++i) issue_frag_read(i, 0, 0, 0);
+            for (int kt = 0; kt + 1 < KT; ++kt) k_tile(kt, std::false_type());
+            k_tile(KT - 1, std::true_type());
         }
 
+#ifdef SB_GEMM_TIMELINE
+        if (round < 2 && p.dbg && lane < 52 && (blockIdx.x == 0 || blockIdx.x == 37)) {
+            const unsigned *src =
+                reinterpret_cast<const unsigned *>(smem + S * C::STAGE_BYTES + wave * C::EPI_WAVE_BYTES);
+            unsigned *dst = p.dbg + (((blockIdx.x ? 1 : 0) * 8 + wave) * 2 + round) * 208;
+            for (int i = lane; i < 208; i += 52) dst[i] = src[i];
+        }
+#endif
         const int m_base = tm * C::BM + wm0, n_base = tn * C::BN + wn0;
         const int this_split = split;
 
@@ -243,9 +292,11 @@ __device__ __forceinline__ void gemm_bf16_tn_body(const GemmBf16Args &p) {
         if (have) {
             nKT = stages_of(nsplit);
             set_item_sources(ntm, ntn, nsplit * p.k_per_split);
+            if (loader) {
 #pragma unroll
-            for (int s = 0; s < S; ++s)
-                if (s < nKT) issue_stage(s);
+                for (int s = 0; s < S; ++s)
+                    if (s < nKT) issue_stage(s);
+            }
         }
 
         if (p.splits == 1 && p.out_bf16) {

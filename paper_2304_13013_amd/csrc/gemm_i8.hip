@@ -4,6 +4,22 @@
 namespace sb {
 namespace {
 
+// 128-byte k-steps (whole cache lines per row; two LDS stages plus the epilogue patch = 160 KiB) when K allows
+// it: four loader waves with a 3-block wave tile, their SIMD partners take 5 blocks (see the kernel header).  Else
+// 64-byte k-steps with four stages, every wave loading.
+typedef GemmI8Cfg<128, 2, 4, 3> K128;
+typedef GemmI8Cfg<64, 4, 8, 4> K64;
+
+#define SB_GEMM_I8_ENTRY(name, CFG, OUT) \
+    __global__ __launch_bounds__(CFG::THREADS) void name(GemmI8Args p) { gemm_i8_dequant_body<CFG, OUT>(p); }
+SB_GEMM_I8_ENTRY(gemm_i8_k128_bf16, K128, OUT_BF16)
+SB_GEMM_I8_ENTRY(gemm_i8_k128_f32, K128, OUT_F32)
+SB_GEMM_I8_ENTRY(gemm_i8_k128_i32, K128, OUT_I32)
+SB_GEMM_I8_ENTRY(gemm_i8_k64_bf16, K64, OUT_BF16)
+SB_GEMM_I8_ENTRY(gemm_i8_k64_f32, K64, OUT_F32)
+SB_GEMM_I8_ENTRY(gemm_i8_k64_i32, K64, OUT_I32)
+#undef SB_GEMM_I8_ENTRY
+
 int cached_num_cu() {
     static int n = 0;
     if (n == 0) {
@@ -16,29 +32,39 @@ int cached_num_cu() {
     return n;
 }
 
+template <class C>
+hipError_t launch(void (*kernel)(GemmI8Args), bool *attr_set, GemmI8Args args, hipStream_t stream) {
+    if (!*attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+        if (e != hipSuccess) return e;
+        *attr_set = true;
+    }
+    int grid = 0;
+    gemm_i8_prepare<C>(args, cached_num_cu(), &grid);
+    kernel<<<grid, C::THREADS, C::LDS_BYTES, stream>>>(args);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t launch_gemm_i8_dequant(const int8_t *aq, const float *state_row, const int8_t *bq,
                                   const float *state_tensor, int64_t M, int64_t N, int64_t K, void *out,
                                   sb_dtype out_dtype, hipStream_t stream) {
     if (M == 0 || N == 0) return hipSuccess;
-    GemmI8Args args{aq, bq, state_row, state_tensor, out, (int)M, (int)N, (int)K, 0, 0, 8, 0};
-    // 256x256 tile.  128-byte k-steps (whole cache lines per row; two LDS stages plus the epilogue patch = 160 KiB)
-    // when K allows it, else 64-byte k-steps with three stages.
-    typedef GemmI8Cfg<256, 256, 128, 2, 4, 2, 1, 0, 0, 2, 1> K128;  // requests spread over two k-step groups, MFMA priority
-    typedef GemmI8Cfg<256, 256, 64, 2, 4, 3, 0> K64;
-    const int ncu = cached_num_cu();
+    GemmI8Args args{aq, bq, state_row, state_tensor, out, (int)M, (int)N, (int)K, 0, 0, 8};
+    static bool attr_set[6] = {false, false, false, false, false, false};
     const bool wide = K % 128 == 0;
     switch (out_dtype) {
         case SB_BF16:
-            return wide ? launch_gemm_i8_cfg<K128, OUT_BF16>(args, ncu, stream)
-                        : launch_gemm_i8_cfg<K64, OUT_BF16>(args, ncu, stream);
+            return wide ? launch<K128>(gemm_i8_k128_bf16, &attr_set[0], args, stream)
+                        : launch<K64>(gemm_i8_k64_bf16, &attr_set[3], args, stream);
         case SB_F32:
-            return wide ? launch_gemm_i8_cfg<K128, OUT_F32>(args, ncu, stream)
-                        : launch_gemm_i8_cfg<K64, OUT_F32>(args, ncu, stream);
+            return wide ? launch<K128>(gemm_i8_k128_f32, &attr_set[1], args, stream)
+                        : launch<K64>(gemm_i8_k64_f32, &attr_set[4], args, stream);
         default:
-            return wide ? launch_gemm_i8_cfg<K128, OUT_I32>(args, ncu, stream)
-                        : launch_gemm_i8_cfg<K64, OUT_I32>(args, ncu, stream);
+            return wide ? launch<K128>(gemm_i8_k128_i32, &attr_set[2], args, stream)
+                        : launch<K64>(gemm_i8_k64_i32, &attr_set[5], args, stream);
     }
 }
 

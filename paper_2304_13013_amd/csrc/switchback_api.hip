@@ -13,8 +13,9 @@ bool ok_dtype(int d) { return d == SB_BF16 || d == SB_F32 || d == SB_I32_RAW; }
 int layer_shape_status(int64_t b, int64_t n, int64_t m) {
     if (b < 0 || n <= 0 || m <= 0) return SB_INVALID_ARG;
     if (n % 64 || m % 64 || b > (int64_t)1 << 30 || n > kMaxIntK || m > kMaxIntK) return SB_UNSUPPORTED_SHAPE;
-    // The weight-gradient kernel addresses dY and X through 32-bit buffer offsets (with a stage of slack).
-    if ((b + 128) * n * 2 >= (int64_t)1 << 32 || (b + 128) * m * 2 >= (int64_t)1 << 32) return SB_UNSUPPORTED_SHAPE;
+    // The GEMM kernels address their operands through 32-bit buffer offsets (with a stage or tile of slack); the
+    // bf16 operands of the weight gradient are the largest.
+    if ((b + 256) * n * 2 >= (int64_t)1 << 32 || (b + 256) * m * 2 >= (int64_t)1 << 32) return SB_UNSUPPORTED_SHAPE;
     return SB_OK;
 }
 
@@ -52,6 +53,8 @@ int switchback_matmul_int8_dequant(const int8_t *aq, const float *state_row, con
                                    sb_dtype out_dtype, void *stream) {
     if (M < 0 || N <= 0 || K <= 0 || !ok_dtype(out_dtype)) return SB_INVALID_ARG;
     if (K % 64 || N % 64 || K > kMaxIntK || N > kMaxIntK || M > (int64_t)1 << 30) return SB_UNSUPPORTED_SHAPE;
+    // 32-bit buffer offsets, with a tile of slack for the rows past the end that read as zero.
+    if ((M + 256) * K >= (int64_t)1 << 32 || (N + 256) * K >= (int64_t)1 << 32) return SB_UNSUPPORTED_SHAPE;
     if (M == 0) return SB_OK;
     if (!ok_ptr(aq) || !ok_ptr(bq) || !ok_ptr(out)) return SB_INVALID_ARG;
     if (out_dtype != SB_I32_RAW && (state_row == nullptr || state_tensor == nullptr)) return SB_INVALID_ARG;
