@@ -7,8 +7,8 @@ namespace {
 // 128-byte k-steps (whole cache lines per row; two LDS stages plus the epilogue patch = 160 KiB) when K allows
 // it: four loader waves with a 3-block wave tile, their SIMD partners take 5 blocks (see the kernel header).  Else
 // 64-byte k-steps with four stages, every wave loading.
-typedef GemmI8Cfg<128, 2, 4, 3> K128;
-typedef GemmI8Cfg<64, 4, 8, 4> K64;
+typedef GemmI8Cfg<128, 2, 4, 3, 1> K128;
+typedef GemmI8Cfg<64, 4, 8, 4, 1> K64;
 
 #define SB_GEMM_I8_ENTRY(name, CFG, OUT) \
     __global__ __launch_bounds__(CFG::THREADS) void name(GemmI8Args p) { gemm_i8_dequant_body<CFG, OUT>(p); }

@@ -39,8 +39,9 @@ namespace sb {
 
 enum { OUT_BF16 = 0, OUT_F32 = 1, OUT_I32 = 2 };
 
-template <int BK_, int STAGES_, int LOADERS_, int MT_LOADER_ = 4>
+template <int BK_, int STAGES_, int LOADERS_, int MT_LOADER_ = 4, int STORE_NT_ = 0>
 struct GemmI8Cfg {
+    static constexpr int STORE_NT = STORE_NT_;  // 1: non-temporal output stores (the output should not evict operand panels from L2)
     static constexpr int BM = 256, BN = 256, BK = BK_, STAGES = STAGES_;
     static constexpr int WAVES_M = 2, WAVES_N = 4, NWAVES = 8, THREADS = NWAVES * 64;
     static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;  // wave tile 128 x 64
@@ -186,18 +187,13 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
     auto set_tile_sources = [&](int tm, int tn) {
         tile_soff = (unsigned)(loads_a ? tm * C::BM : tn * C::BN) * (unsigned)p.K;
     };
-    auto issue_stage = [&](int kt) {
-        unsigned char *dst = smem + (kt % S) * C::STAGE_BYTES + wave * C::RPL * C::BK;
+    auto issue_stage = [&](int slot, int kt) {
+        unsigned char *dst = smem + slot * C::STAGE_BYTES + wave * C::RPL * C::BK;
         const unsigned soff = tile_soff + (unsigned)kt * C::BK;
 #pragma unroll
         for (int i = 0; i < C::LPW; ++i)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)(dst + i * 1024), 16, voff[i % C::NVAR],
                                                      soff + (unsigned)i * req_step, 0, 0);
-    };
-    auto issue_prologue = [&]() {
-#pragma unroll
-        for (int s = 0; s < S; ++s)
-            if (s < KT) issue_stage(s);
     };
 
     // MFMA operand fragments, double-buffered in registers.  A k-step group issues its MFMAs in the order
@@ -207,9 +203,9 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
     const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
     static_assert((C::BM + C::BN) * C::BK <= 65536, "fragment offsets must fit the 16-bit ds offset field");
     const unsigned x_off = wm0 * C::BK, w_off = (C::BM + wn0) * C::BK;
-    // i-th fragment read of the group (k-tile kt, k-step kk) into register buffer buf.
-    auto issue_frag_read = [&](int i, int buf, int kt, int kk) {
-        const unsigned at = lds_base + (kt % S) * C::STAGE_BYTES + frag_off[kk];
+    // i-th fragment read of the group (stage in LDS slot `slot`, k-step kk) into register buffer buf.
+    auto issue_frag_read = [&](int i, int buf, int slot, int kk) {
+        const unsigned at = lds_base + slot * C::STAGE_BYTES + frag_off[kk];
         switch (i) {
             case 0: wf[buf][0] = lds_read_b128<0>(at + w_off); break;
             case 1: xf[buf][0] = lds_read_b128<0>(at + x_off); break;
@@ -250,16 +246,79 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
     if (OUT != OUT_I32) tensor_scale = p.state_tensor[0] / 16129.0f;
     asm volatile("" : "+v"(tensor_scale));
 
-    int tm, tn;
-    bool have = gemm_tile_of(blockIdx.x, 0, gridDim.x, p.tiles_m, p.tiles_n, p.group_m, &tm, &tn);
-    if (have && loader) {
-        set_tile_sources(tm, tn);
-        issue_prologue();
-    }
-    // Whether the previous tile's EPI_STORES output stores sit right behind this tile's pre-requested stages in
-    // the vector-memory queue (false when unknown, which only makes the waits stricter).
-    bool stores_behind_prologue = false;
+    // ---- Work list.  A segment is the k-tile range [kb, ke) of one output tile; segment i of this workgroup is the
+    // tile of its i-th round of the tile walk, whole.
+    struct Seg {
+        int tm, tn, kb, ke;
+    };
+    auto segment_of = [&](int i, Seg &sg) -> bool {
+        if (!gemm_tile_of(blockIdx.x, i, gridDim.x, p.tiles_m, p.tiles_n, p.group_m, &sg.tm, &sg.tn)) return false;
+        sg.kb = 0;
+        sg.ke = KT;
+        return true;
+    };
 
+    // ---- Vector-memory bookkeeping.  younger[s] counts the vector-memory operations this wave has issued after the
+    // requests of the stage now in LDS slot s (younger_scale: after the row-scale loads of the current segment).
+    // The operations of a wave retire in order, so "at most younger[s] outstanding" means that stage has landed,
+    // whatever else (later stages, output stores, scale loads) is still in flight behind it.
+    int younger[S], younger_scale = 0;
+#pragma unroll
+    for (int i = 0; i < S; ++i) younger[i] = 0;
+    auto note_vmem = [&](int n) {
+#pragma unroll
+        for (int i = 0; i < S; ++i) younger[i] += n;
+        younger_scale += n;
+    };
+    auto wait_vmem_at_most = [&](int n) {
+        switch (n < 63 ? n : 63) {
+#define SB_CASE4(b) case b: wait_vmcnt<b>(); break; case b + 1: wait_vmcnt<b + 1>(); break; \
+                    case b + 2: wait_vmcnt<b + 2>(); break; case b + 3: wait_vmcnt<b + 3>(); break;
+            SB_CASE4(0) SB_CASE4(4) SB_CASE4(8) SB_CASE4(12) SB_CASE4(16) SB_CASE4(20) SB_CASE4(24) SB_CASE4(28)
+            SB_CASE4(32) SB_CASE4(36) SB_CASE4(40) SB_CASE4(44) SB_CASE4(48) SB_CASE4(52) SB_CASE4(56) SB_CASE4(60)
+#undef SB_CASE4
+        }
+    };
+    auto wait_slot_landed = [&](int slot) {
+        int n = 0;
+#pragma unroll
+        for (int i = 0; i < S; ++i) n = slot == i ? younger[i] : n;
+        wait_vmem_at_most(n);
+    };
+
+    // ---- Load cursor: runs STAGES stages ahead of the MFMAs, across segment boundaries, so a new tile's first
+    // stages are requested during the last k-tiles of the one before it.  Every wave advances the cursor; only the
+    // loader waves issue.
+    Seg ls;
+    int l_idx = 0, l_g = 0;  // segment being loaded; global count of stages requested so far (stage g lives in slot g % S)
+    bool l_have = segment_of(0, ls);
+    int l_kt = l_have ? ls.kb : 0;
+    if (l_have) set_tile_sources(ls.tm, ls.tn);
+    auto issue_next = [&]() {
+        if (!l_have) return;
+        const int slot = l_g % S;
+        if (loader) {
+            issue_stage(slot, l_kt);
+            note_vmem(C::LPW);
+#pragma unroll
+            for (int i = 0; i < S; ++i) younger[i] = slot == i ? 0 : younger[i];
+        }
+        ++l_g;
+        if (++l_kt == ls.ke) {
+            l_have = segment_of(++l_idx, ls);
+            if (l_have) {
+                l_kt = ls.kb;
+                set_tile_sources(ls.tm, ls.tn);
+            }
+        }
+    };
+#pragma unroll
+    for (int i = 0; i < S; ++i) issue_next();
+
+    Seg cs;
+    bool have = segment_of(0, cs);
+    int g = 0;  // global index of the stage the MFMAs work on
+    bool first = true;
 #ifdef SB_GEMM_TIMELINE
     unsigned dbg_epi_end = 0, dbg_prologue_issued = 0;
 #endif
@@ -281,59 +340,59 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[mt][nt][r] = 0;
 
-        // Stage 0 of this tile: behind it sit the other pre-requested stages (and the previous tile's stores).
-        int issued_upto = min(S - 1, KT - 1);
-        if (loader) {
-            if (stores_behind_prologue)
-                wait_stage<C::LPW, EPI_STORES>(issued_upto);
-            else
-                wait_stage<C::LPW, 0>(issued_upto);
-        }
-        block_barrier();
-        SB_STAMP(200);
-        // Row absmax values of this tile, fetched now so that the epilogue finds them in registers.  They queue
-        // behind the pre-requested stages (and the previous tile's stores) and ahead of every in-loop request.
+        Seg ns;
+        const bool next_have = segment_of(round + 1, ns);
+        const int tm = cs.tm, tn = cs.tn;
+
+        // Row absmax values of this tile, requested now so that the epilogue finds them in registers.  Inline asm with
+        // a counted wait: the compiler's own wait would drain the stages in flight.
         float srow[MT];
         if (OUT != OUT_I32) {
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-                srow[mt] = p.state_row[min(tm * C::BM + wm0 + mt * 32 + frow, p.M - 1)];
+            for (int mt = 0; mt < MT; ++mt) {
+                const float *src = p.state_row + min(tm * C::BM + wm0 + mt * 32 + frow, p.M - 1);
+                asm volatile("global_load_dword %0, %1, off" : "=v"(srow[mt]) : "v"(src) : "memory");
+            }
+            note_vmem(NSCALE);
+            younger_scale = 0;
         }
+        if (first) {
+            // The very first stage: nothing was read before it, so no hand-over has waited for it yet.
+            if (loader) wait_slot_landed(0);
+            block_barrier();
 #pragma unroll
-        for (int i = 0; i < NFRAG; ++i) issue_frag_read(i, 0, 0, 0);
+            for (int i = 0; i < NFRAG; ++i) issue_frag_read(i, 0, 0, 0);
+            first = false;
+        }
+        SB_STAMP(200);
 
-        // One k-tile (stage).  The tile's last k-tile is a separate instantiation, so that "another k-step group
-        // follows" is known at compile time and the hot loop carries no branches for it.
-        auto k_tile = [&](const int kt, auto is_last_tile) {
-            constexpr bool last_tile = decltype(is_last_tile)::value;
+        // One k-tile (stage g).  Its last k-step group hands the stage over and already reads the next stage's first
+        // fragments, also when that stage belongs to the next segment.  The very last stage of the workgroup is a
+        // separate instantiation, so that "another k-step group follows" is known at compile time and the hot loop
+        // carries no branches for it.
+        auto k_tile = [&](const int kt, auto is_last_stage) __attribute__((always_inline)) {
+            constexpr bool last_stage = decltype(is_last_stage)::value;
+            const int slot = g % S, next_slot = (g + 1) % S;
 #pragma unroll
             for (int kk = 0; kk < C::KK; ++kk) {
                 const bool last_group = kk + 1 == C::KK;
-                const bool has_next = !last_group || !last_tile;  // another k-step group follows in this tile
+                const bool has_next = !last_group || !last_stage;  // another k-step group follows
                 const bool handed_over = last_group && has_next;
                 if (handed_over) {
-                    // Hand-over: the fragments of this last k-step of stage kt are in (or on their way to)
-                    // registers.  Retire this wave's LDS reads, make sure stage kt+1 has landed, then refill the
-                    // freed stage.
+                    // Hand-over: the fragments of this last k-step of the stage are in (or on their way to)
+                    // registers.  Retire this wave's LDS reads, make sure the next stage has landed, then refill
+                    // the freed slot.
                     SB_STAMP_AT(12, kt * 4 + 0);
-                    if (loader) {
-                        if (kt + 1 >= S)
-                            wait_stage<C::LPW, 0>(issued_upto - (kt + 1));
-                        else if (stores_behind_prologue)
-                            wait_stage<C::LPW, EPI_STORES + NSCALE>(issued_upto - (kt + 1));
-                        else
-                            wait_stage<C::LPW, NSCALE>(issued_upto - (kt + 1));
-                    }
+                    if (loader) wait_slot_landed(next_slot);
                     SB_STAMP_AT(13, kt * 4 + 0);
                     wait_lds_reads();
                     SB_STAMP_AT(14, kt * 4 + 0);
                     block_barrier();
                     SB_STAMP(kt * 4 + 3);
-                    if (loader && kt + S < KT) issue_stage(kt + S);
-                    issued_upto = min(KT - 1, kt + S);
+                    issue_next();
                 }
                 const int cur = kk & 1, nxt = (kk + 1) & 1;
-                const int next_kt = last_group ? kt + 1 : kt, next_kk = last_group ? 0 : kk + 1;
+                const int read_slot = last_group ? next_slot : slot, next_kk = last_group ? 0 : kk + 1;
                 SB_STAMP_AT(kk * 3 + 0, kt * 4 + 0);
                 int landed = 0;  // fragments of this group known to have landed
 #pragma unroll
@@ -354,14 +413,16 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
                     }
                     if (idx == 1) SB_STAMP_AT(kk * 3 + 1, kt * 4 + 0);
                     acc[mt][nt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[cur][nt], xf[cur][mt], acc[mt][nt], 0, 0, 0);
-                    if (idx < NFRAG && has_next) issue_frag_read(idx, nxt, next_kt, next_kk);
+                    if (idx < NFRAG && has_next) issue_frag_read(idx, nxt, read_slot, next_kk);
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 SB_STAMP_AT(kk * 3 + 2, kt * 4 + 0);
             }
+            ++g;
         };
-        for (int kt = 0; kt + 1 < KT; ++kt) k_tile(kt, std::false_type());
-        k_tile(KT - 1, std::true_type());
+        const int nkt = cs.ke - cs.kb;
+        for (int kt = 0; kt < (next_have ? nkt : nkt - 1); ++kt) k_tile(kt, std::false_type());
+        if (!next_have) k_tile(nkt - 1, std::true_type());
 
         SB_STAMP(201);
 #ifdef SB_GEMM_TIMELINE
@@ -375,6 +436,7 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
             for (int i = lane; i < 208; i += 52)
                 dst[i] = i == 204 ? dbg_epi_end : i == 205 ? dbg_prologue_issued : src[i];
         }
+        dbg_prologue_issued = (unsigned)__builtin_readcyclecounter();
 #endif
         const int m_base = tm * C::BM + wm0, n_base = tn * C::BN + wn0;
         const bool interior = (tm + 1) * C::BM <= p.M && (tn + 1) * C::BN <= p.N;
@@ -382,31 +444,15 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
         // Row scales r_i = state_row[i] * (state_tensor / 127^2), one per lane per 32-row block.
         float rscale[MT];
         if (OUT != OUT_I32) {
+            wait_vmem_at_most(younger_scale);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) asm volatile("" : "+v"(srow[mt]));
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) rscale[mt] = srow[mt] * tensor_scale;
-            // Pin the scales (and the wait for their loads) in front of the requests issued below, so that the
-            // epilogue does not have to wait for the next tile's stages.
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) asm volatile("" : "+v"(rscale[mt]));
         }
 
-        // Every wave is done reading the stages: the loader waves request the next tile's first stages, then
-        // everybody runs the epilogue while they are in flight.
-        wait_lds_reads();
-        block_barrier();
-        int ntm, ntn;
-        have = gemm_tile_of(blockIdx.x, round + 1, gridDim.x, p.tiles_m, p.tiles_n, p.group_m, &ntm, &ntn);
-        if (have && loader) {
-            set_tile_sources(ntm, ntn);
-            issue_prologue();
-        }
-#ifdef SB_GEMM_TIMELINE
-        dbg_prologue_issued = (unsigned)__builtin_readcyclecounter();
-#endif
-        // The wait counts of the next main loop assume these requests precede the output stores below.
-        __builtin_amdgcn_sched_barrier(0);
-        asm volatile("" ::: "memory");
-
+        // The epilogue needs no barrier: the patch is private to the wave, and the next segment's first stages are
+        // already in flight (or landed).
         if (OUT == OUT_BF16) {
             unsigned short *out = static_cast<unsigned short *>(p.out);
             unsigned char *epi = smem + S * C::STAGE_BYTES + wave * C::EPI_WAVE_BYTES;
@@ -415,25 +461,32 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
 #pragma unroll
                 for (int nt = 0; nt < C::NT; ++nt)
 #pragma unroll
-                    for (int g = 0; g < 4; ++g) {
+                    for (int q = 0; q < 4; ++q) {
                         v4f v;
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) v[e] = (float)acc[mt][nt][4 * g + e] * rscale[mt];
-                        const int piece = (nt * 4 + g) ^ (frow & 7);
+                        for (int e = 0; e < 4; ++e) v[e] = (float)acc[mt][nt][4 * q + e] * rscale[mt];
+                        const int piece = (nt * 4 + q) ^ (frow & 7);
                         *reinterpret_cast<v4bf *>(epi + frow * (C::WTN * 2) + piece * 16 + fhalf * 8) =
                             __builtin_convertvector(v, v4bf);
                     }
 #pragma unroll
-                for (int j = 0; j < C::EPI_WAVE_BYTES / 1024; ++j) {
+                for (int j = 0; j < C::STORES_PER_BLOCK; ++j) {
                     const int idx = j * 64 + lane;
                     const int prow = idx / C::EPI_PIECES, piece = idx % C::EPI_PIECES;
                     const v4u val = *reinterpret_cast<const v4u *>(epi + prow * (C::WTN * 2) +
                                                                    ((piece ^ (prow & 7)) << 4));
                     const int gr = m_base + mt * 32 + prow, gc = n_base + piece * 8;
-                    if (interior || (gr < p.M && gc < p.N))
-                        *reinterpret_cast<v4u *>(out + (int64_t)gr * p.N + gc) = val;
+                    if (interior || (gr < p.M && gc < p.N)) {
+                        if (C::STORE_NT)
+                            __builtin_nontemporal_store(val, reinterpret_cast<v4u *>(out + (int64_t)gr * p.N + gc));
+                        else
+                            *reinterpret_cast<v4u *>(out + (int64_t)gr * p.N + gc) = val;
+                    }
                 }
             }
+            // Count the stores only where every one of them is certain to have been issued: an overcount would
+            // loosen later waits, an undercount merely makes them stricter.
+            if (interior) note_vmem(EPI_STORES);
         } else {
             // Verification paths: binary32 results or raw accumulators, stored straight from the registers.
 #pragma unroll
@@ -441,18 +494,18 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
 #pragma unroll
                 for (int nt = 0; nt < C::NT; ++nt)
 #pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const int gr = m_base + mt * 32 + frow, gc = n_base + nt * 32 + 8 * g + 4 * fhalf;
+                    for (int q = 0; q < 4; ++q) {
+                        const int gr = m_base + mt * 32 + frow, gc = n_base + nt * 32 + 8 * q + 4 * fhalf;
                         if (gr < p.M && gc < p.N) {
                             if (OUT == OUT_F32) {
                                 v4f v;
 #pragma unroll
-                                for (int e = 0; e < 4; ++e) v[e] = (float)acc[mt][nt][4 * g + e] * rscale[mt];
+                                for (int e = 0; e < 4; ++e) v[e] = (float)acc[mt][nt][4 * q + e] * rscale[mt];
                                 *reinterpret_cast<v4f *>(static_cast<float *>(p.out) + (int64_t)gr * p.N + gc) = v;
                             } else {
                                 v4i v;
 #pragma unroll
-                                for (int e = 0; e < 4; ++e) v[e] = acc[mt][nt][4 * g + e];
+                                for (int e = 0; e < 4; ++e) v[e] = acc[mt][nt][4 * q + e];
                                 *reinterpret_cast<v4i *>(static_cast<int *>(p.out) + (int64_t)gr * p.N + gc) = v;
                             }
                         }
@@ -461,9 +514,8 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
 #ifdef SB_GEMM_TIMELINE
         dbg_epi_end = (unsigned)__builtin_readcyclecounter();
 #endif
-        stores_behind_prologue = (OUT == OUT_BF16) && interior;
-        tm = ntm;
-        tn = ntn;
+        cs = ns;
+        have = next_have;
     }
 }
 
