@@ -15,7 +15,7 @@
  *   - Shapes: b >= 1 (0 is accepted and is a no-op), n % 64 == 0, m % 64 == 0, and the contraction length of
  *     the int8 products (n for forward, m for the input gradient) at most 131072 so that 127^2 * K < 2^31.
  *     The GEMM kernels use 32-bit byte offsets into an operand: (b + 256) * max(n, m) * 2 must stay below 2^32
- *     (for the int8 product alone: (M + 256) * K and (N + 256) * K below 2^32).
+ *     (for the int8 product alone: (M + 256) * K, (N + 256) * K and 2 * M * N below 2^32).
  *   - Inputs must be finite; NaN/Inf give unspecified values but never a fault.  There is no bias (Algorithm 1
  *     passes only the weight).
  *   - Return value: SB_OK or an error code; nothing is enqueued when an error is returned, except
@@ -88,7 +88,7 @@ int switchback_quantize_tensorwise(const void *w_bf16, int64_t rows, int64_t col
  * evaluated in binary32 as c = state_tensor/16129, r_i = state_row[i]*c, out = (float)acc * r_i, then rounded
  * to nearest-even when out_dtype is SB_BF16.  Both operands have the contraction index contiguous.
  *   aq [M,K] int8; state_row [M] f32; bq [N,K] int8; state_tensor [1] f32 (device); out [M,N].
- *   K % 64 == 0, N % 64 == 0, K <= 131072, (M + 256) * K < 2^32, (N + 256) * K < 2^32.  With SB_I32_RAW the states are ignored (may be NULL). */
+ *   K % 64 == 0, N % 64 == 0, K <= 131072, (M + 256) * K < 2^32, (N + 256) * K < 2^32, 2 * M * N < 2^32.  With SB_I32_RAW the states are ignored (may be NULL). */
 int switchback_matmul_int8_dequant(const int8_t *aq, const float *state_row, const int8_t *bq,
                                    const float *state_tensor, int64_t M, int64_t N, int64_t K, void *out,
                                    sb_dtype out_dtype, void *stream);

@@ -241,6 +241,10 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
         }
     };
 
+    // Output (bf16 path) through a buffer resource: 32-bit offsets, the tile part scalar.
+    const __amdgpu_buffer_rsrc_t rsrc_out =
+        __builtin_amdgcn_make_buffer_rsrc(p.out, 0, (unsigned)((size_t)p.M * p.N * 2), 0x00020000);
+
     // c = state_tensor / 127^2, read once (the pointer may alias nothing the kernel writes).
     float tensor_scale = 0.0f;
     if (OUT != OUT_I32) tensor_scale = p.state_tensor[0] / 16129.0f;
@@ -357,19 +361,23 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
             younger_scale = 0;
         }
         if (first) {
-            // The very first stage: nothing was read before it, so no hand-over has waited for it yet.
-            if (loader) wait_slot_landed(0);
+            // (Re)start of the fragment pipeline: the very first stage, or the stage after a segment that ended
+            // without a hand-over.  Nobody has waited for this stage yet, and the slot of the stage before it (if
+            // any) has not been refilled.
+            if (loader) wait_slot_landed(g % S);
+            wait_lds_reads();
             block_barrier();
+            if (l_g < g + S) issue_next();
 #pragma unroll
-            for (int i = 0; i < NFRAG; ++i) issue_frag_read(i, 0, 0, 0);
+            for (int i = 0; i < NFRAG; ++i) issue_frag_read(i, 0, g % S, 0);
             first = false;
         }
         SB_STAMP(200);
 
         // One k-tile (stage g).  Its last k-step group hands the stage over and already reads the next stage's first
-        // fragments, also when that stage belongs to the next segment.  The very last stage of the workgroup is a
-        // separate instantiation, so that "another k-step group follows" is known at compile time and the hot loop
-        // carries no branches for it.
+        // fragments, also when that stage belongs to the next segment.  A stage that ends the fragment pipeline (the
+        // workgroup's last one) is a separate instantiation, so that "another k-step group follows" is known at
+        // compile time and the hot loop carries no branches for it.
         auto k_tile = [&](const int kt, auto is_last_stage) __attribute__((always_inline)) {
             constexpr bool last_stage = decltype(is_last_stage)::value;
             const int slot = g % S, next_slot = (g + 1) % S;
@@ -453,35 +461,42 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
 
         // The epilogue needs no barrier: the patch is private to the wave, and the next segment's first stages are
         // already in flight (or landed).
+        {
+        // The lane-dependent addresses of the epilogue are recomputed here from an opaque copy of the lane id, so that
+        // the compiler does not keep them in registers through the main loop, where every register counts.
+        int lane_e = lane;
+        asm volatile("" : "+v"(lane_e));
+        const int frow = lane_e & 31, fhalf = lane_e >> 5;
         if (OUT == OUT_BF16) {
-            unsigned short *out = static_cast<unsigned short *>(p.out);
             unsigned char *epi = smem + S * C::STAGE_BYTES + wave * C::EPI_WAVE_BYTES;
+            const unsigned epi_voff = (unsigned)((lane_e / C::EPI_PIECES) * p.N + (lane_e % C::EPI_PIECES) * 8) * 2;
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
-                for (int nt = 0; nt < C::NT; ++nt)
+                for (int nt = 0; nt < C::NT; ++nt) {
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
                         v4f v;
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) v[e] = (float)acc[mt][nt][4 * q + e] * rscale[mt];
+                        for (int e = 0; e < 4; ++e)
+                            v[e] = (float)(acc[mt][nt][4 * q + e]) * rscale[mt];
                         const int piece = (nt * 4 + q) ^ (frow & 7);
                         *reinterpret_cast<v4bf *>(epi + frow * (C::WTN * 2) + piece * 16 + fhalf * 8) =
                             __builtin_convertvector(v, v4bf);
                     }
+                }
 #pragma unroll
                 for (int j = 0; j < C::STORES_PER_BLOCK; ++j) {
-                    const int idx = j * 64 + lane;
+                    const int idx = j * 64 + lane_e;
                     const int prow = idx / C::EPI_PIECES, piece = idx % C::EPI_PIECES;
                     const v4u val = *reinterpret_cast<const v4u *>(epi + prow * (C::WTN * 2) +
                                                                    ((piece ^ (prow & 7)) << 4));
                     const int gr = m_base + mt * 32 + prow, gc = n_base + piece * 8;
-                    if (interior || (gr < p.M && gc < p.N)) {
-                        if (C::STORE_NT)
-                            __builtin_nontemporal_store(val, reinterpret_cast<v4u *>(out + (int64_t)gr * p.N + gc));
-                        else
-                            *reinterpret_cast<v4u *>(out + (int64_t)gr * p.N + gc) = val;
-                    }
+                    // Row block j of this 32-row block starts (64 / EPI_PIECES) * j rows down; the lane's place inside
+                    // it is the per-lane constant epi_voff.
+                    const unsigned soff = (unsigned)((m_base + mt * 32 + j * (64 / C::EPI_PIECES)) * p.N + n_base) * 2;
+                    if (interior || (gr < p.M && gc < p.N))
+                        __builtin_amdgcn_raw_buffer_store_b128(val, rsrc_out, epi_voff, soff, C::STORE_NT ? 2 : 0);
                 }
             }
             // Count the stores only where every one of them is certain to have been issued: an overcount would
@@ -490,9 +505,9 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
         } else {
             // Verification paths: binary32 results or raw accumulators, stored straight from the registers.
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
+            for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
-                for (int nt = 0; nt < C::NT; ++nt)
+                for (int nt = 0; nt < C::NT; ++nt) {
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
                         const int gr = m_base + mt * 32 + frow, gc = n_base + nt * 32 + 8 * q + 4 * fhalf;
@@ -500,16 +515,21 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
                             if (OUT == OUT_F32) {
                                 v4f v;
 #pragma unroll
-                                for (int e = 0; e < 4; ++e) v[e] = (float)acc[mt][nt][4 * q + e] * rscale[mt];
+                                for (int e = 0; e < 4; ++e)
+                                    v[e] = (float)(acc[mt][nt][4 * q + e]) * rscale[mt];
                                 *reinterpret_cast<v4f *>(static_cast<float *>(p.out) + (int64_t)gr * p.N + gc) = v;
                             } else {
                                 v4i v;
 #pragma unroll
-                                for (int e = 0; e < 4; ++e) v[e] = acc[mt][nt][4 * q + e];
+                                for (int e = 0; e < 4; ++e)
+                                    v[e] = acc[mt][nt][4 * q + e];
                                 *reinterpret_cast<v4i *>(static_cast<int *>(p.out) + (int64_t)gr * p.N + gc) = v;
                             }
                         }
                     }
+                }
+            }
+        }
         }
 #ifdef SB_GEMM_TIMELINE
         dbg_epi_end = (unsigned)__builtin_readcyclecounter();
@@ -534,12 +554,11 @@ __device__ __forceinline__ void gemm_i8_dequant_body(const GemmI8Args &p) {
 
 // Launch geometry shared by the entry points: persistent grid, a multiple of the XCD count.
 template <class C>
-inline void gemm_i8_prepare(GemmI8Args &a, int num_cu, int *grid) {
+inline void gemm_i8_prepare(GemmI8Args &a, int workgroups, int *grid) {
     a.tiles_m = (a.M + C::BM - 1) / C::BM;
     a.tiles_n = (a.N + C::BN - 1) / C::BN;
     if (a.group_m <= 0) a.group_m = 8;
-    int g = num_cu - num_cu % 8;
-    *grid = g < 8 ? 8 : g;
+    *grid = workgroups;
 }
 
 }  // namespace sb

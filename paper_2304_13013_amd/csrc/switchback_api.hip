@@ -55,6 +55,7 @@ int switchback_matmul_int8_dequant(const int8_t *aq, const float *state_row, con
     if (K % 64 || N % 64 || K > kMaxIntK || N > kMaxIntK || M > (int64_t)1 << 30) return SB_UNSUPPORTED_SHAPE;
     // 32-bit buffer offsets, with a tile of slack for the rows past the end that read as zero.
     if ((M + 256) * K >= (int64_t)1 << 32 || (N + 256) * K >= (int64_t)1 << 32) return SB_UNSUPPORTED_SHAPE;
+    if (M * N * 2 >= (int64_t)1 << 32) return SB_UNSUPPORTED_SHAPE;  // the output too
     if (M == 0) return SB_OK;
     if (!ok_ptr(aq) || !ok_ptr(bq) || !ok_ptr(out)) return SB_INVALID_ARG;
     if (out_dtype != SB_I32_RAW && (state_row == nullptr || state_tensor == nullptr)) return SB_INVALID_ARG;
