@@ -37,12 +37,15 @@ struct GemmBf16Args {
 #endif
 };
 
-template <int STAGES_ = 2, int LOADERS_ = 4>
+template <int STAGES_ = 2, int LOADERS_ = 4, int MT_LOADER_ = 4, int BKT_ = 64>
 struct GemmBf16Cfg {
-    static constexpr int BM = 256, BN = 256, BKT = 64;  // dW rows (dY columns), dW columns (X columns), tokens/stage
+    static constexpr int MT_LOADER = MT_LOADER_;  // 32-row MFMA blocks of a loader wave's tile; when < 4 its SIMD partner
+                                                  // (wave + 4) takes the other 8 - MT_LOADER blocks of the wave column
+    static constexpr int BM = 256, BN = 256, BKT = BKT_;  // dW rows (dY columns), dW columns (X columns), tokens/stage
+    static constexpr int REQ_OP = BKT / 2;                    // 1 KiB requests (two token rows) per operand tile
     static constexpr int STAGES = STAGES_, LOADERS = LOADERS_;
     static constexpr int WAVES_M = 2, WAVES_N = 4, NWAVES = 8, THREADS = 512;
-    static constexpr int WTM = 128, WTN = 64, MT = 4, NT = 2;
+    static constexpr int WTM = 128, WTN = 64, NT = 2;
     static constexpr int KK = BKT / 16;                       // MFMA k-steps (16 tokens) per stage
     static constexpr int OP_BYTES = BKT * 512;                // one operand tile: BKT token rows of 256 bf16
     static constexpr int STAGE_BYTES = 2 * OP_BYTES;          // dY tile then X tile
@@ -50,24 +53,25 @@ struct GemmBf16Cfg {
     static constexpr int EPI_WAVE_BYTES = 32 * WTN * 2, EPI_PIECES = WTN * 2 / 16;
     static constexpr int LDS_BYTES = STAGES * STAGE_BYTES + NWAVES * EPI_WAVE_BYTES;
     static_assert(STAGES >= 2 && LDS_BYTES <= 160 * 1024 && (LOADERS == 4 || LOADERS == 8), "configuration");
+    static_assert(MT_LOADER == 4 || (LOADERS == 4 && MT_LOADER == 3), "uneven split");
+    static_assert((BKT == 64 || BKT == 32) && LPW % 2 == 0 && REQ_OP % LPW == 0, "stage length");
     static_assert(LPW * (STAGES - 1) < 64, "vmcnt range");
 };
 
-// The kernel body; the __global__ entry that calls it lives next to the launcher (a __global__ template that uses
-// device-only buffer builtins does not instantiate in the host pass).
-template <class C>
-__device__ __forceinline__ void gemm_bf16_tn_body(const GemmBf16Args &p) {
+// What one wave does: an (MT*32) x 64 part of the workgroup's tile, rows from wm0.  Every role runs the same
+// sequence of barriers.
+template <class C, int MT>
+__device__ __forceinline__ void gemm_bf16_tn_role(const GemmBf16Args &p, const int wave, const int wm0) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     typedef __attribute__((address_space(3))) void lds_void;
     constexpr int S = C::STAGES;
 
     const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps the buffer resources in SGPRs
-    const int wm0 = (wave / C::WAVES_N) * C::WTM, wn0 = (wave % C::WAVES_N) * C::WTN;
+    const int wn0 = (wave % C::WAVES_N) * C::WTN;
     const int frow = lane & 31, fhalf = lane >> 5;
 
     // Loader role (see the int8 kernel for why only LOADERS waves issue requests, all right after a hand-over).
-    // Request i of loader wave w fills 1 KiB = token rows (2j, 2j+1) of one operand tile, j = (w*LPW + i) % 32; the
+    // Request i of loader wave w fills 1 KiB = token rows (2j, 2j+1) of one operand tile, j = (w*LPW + i) % REQ_OP; the
     // first 32 requests of a stage load dY, the rest X, so a wave loads one operand only.  LDS slot (token, p) holds
     // 16-byte column chunk p ^ ((token & 3) << 2): token rows are 512 bytes apart, so without it the four token rows
     // one transposing read touches would all fall into the same 64-byte bank window.  A lane's byte offset is
@@ -75,13 +79,13 @@ __device__ __forceinline__ void gemm_bf16_tn_body(const GemmBf16Args &p) {
     // Columns past the operand's width (partial tiles) read the next token row or, at the very end, zeros from the
     // bounds check; they only feed results that are never stored.
     const bool loader = wave < C::LOADERS;
-    const bool loads_dy = wave * C::LPW < 32;
+    const bool loads_dy = wave * C::LPW < C::REQ_OP;
     const unsigned ld = loads_dy ? p.m : p.n;  // row length of the operand this wave loads
     // The bounds check of the buffer resource (num_records in bytes) turns token rows past b into zeros.
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
         (void *)(loads_dy ? p.dy : p.x), 0, (unsigned)((size_t)p.b * ld * 2), 0x00020000);
     const int l_tok = lane >> 5, l_pos = lane & 31;
-    const int tok0 = ((wave * C::LPW) % 32) * 2;  // first token row of the wave's share within a stage
+    const int tok0 = ((wave * C::LPW) % C::REQ_OP) * 2;  // first token row of the wave's share within a stage
     unsigned voff[2];
 #pragma unroll
     for (int v = 0; v < 2; ++v) voff[v] = ((unsigned)l_tok * ld + ((l_pos ^ ((2 * v + l_tok) << 2)) << 3)) * 2;
@@ -112,14 +116,14 @@ __device__ __forceinline__ void gemm_bf16_tn_body(const GemmBf16Args &p) {
         const int chunk = (col >> 3) ^ ((f_tok & 3) << 2);
         return op_base + f_tok * 512 + chunk * 16 + (col & 7) * 2;
     };
-    int goff[C::MT], xoff[C::NT];
+    int goff[MT], xoff[C::NT];
 #pragma unroll
-    for (int mt = 0; mt < C::MT; ++mt) goff[mt] = frag_off(0, wm0 + mt * 32);
+    for (int mt = 0; mt < MT; ++mt) goff[mt] = frag_off(0, wm0 + mt * 32);
 #pragma unroll
     for (int nt = 0; nt < C::NT; ++nt) xoff[nt] = frag_off(C::OP_BYTES, wn0 + nt * 32);
     // The transposing reads are inline asm (see gemm_i8_kernel.h): the compiler would otherwise order every LDS read
     // behind ALL outstanding buffer->LDS requests (vmcnt(0)) and use lgkmcnt(0) in front of every MFMA group.
-    v8bf gf[2][C::MT], xf[2][C::NT];
+    v8bf gf[2][MT], xf[2][C::NT];
     const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
     auto read_pair = [&](unsigned addr) -> v8bf {
         v2u lo, hi;
@@ -130,8 +134,8 @@ __device__ __forceinline__ void gemm_bf16_tn_body(const GemmBf16Args &p) {
     // Fragment schedule of the int8 kernel: a k-step group issues its MFMAs in the order (g0,x0) (g0,x1) (g1,x0) ...
     // and reads the next group's fragments in the order x0 g0 x1 g1 g2 g3, one fragment (two transposing reads) after
     // each of its first six MFMAs.
-    static_assert(C::MT == 4 && C::NT == 2, "fragment schedule below is written for 4x2 MFMA blocks per wave");
-    constexpr int NFRAG = C::MT + C::NT;
+    static_assert(C::NT == 2, "fragment schedule below is written for MT x 2 MFMA blocks per wave");
+    constexpr int NFRAG = MT + C::NT;
     auto issue_frag_read = [&](int i, int buf, int kt, int kk) {
         const unsigned base = lds_base + (kt % S) * C::STAGE_BYTES + kk * (16 * 512);
         switch (i) {
@@ -139,8 +143,9 @@ __device__ __forceinline__ void gemm_bf16_tn_body(const GemmBf16Args &p) {
             case 1: gf[buf][0] = read_pair(base + goff[0]); break;
             case 2: xf[buf][1] = read_pair(base + xoff[1]); break;
             case 3: gf[buf][1] = read_pair(base + goff[1]); break;
-            case 4: gf[buf][2] = read_pair(base + goff[2]); break;
-            default: gf[buf][3] = read_pair(base + goff[3]); break;
+            case 4: gf[buf][2 % MT] = read_pair(base + goff[2 % MT]); break;
+            case 5: gf[buf][3 % MT] = read_pair(base + goff[3 % MT]); break;
+            default: gf[buf][4 % MT] = read_pair(base + goff[4 % MT]); break;
         }
     };
     auto pin_frag = [&](int i, int buf) {
@@ -149,8 +154,9 @@ __device__ __forceinline__ void gemm_bf16_tn_body(const GemmBf16Args &p) {
             case 1: asm volatile("" : "+v"(gf[buf][0])); break;
             case 2: asm volatile("" : "+v"(xf[buf][1])); break;
             case 3: asm volatile("" : "+v"(gf[buf][1])); break;
-            case 4: asm volatile("" : "+v"(gf[buf][2])); break;
-            default: asm volatile("" : "+v"(gf[buf][3])); break;
+            case 4: asm volatile("" : "+v"(gf[buf][2 % MT])); break;
+            case 5: asm volatile("" : "+v"(gf[buf][3 % MT])); break;
+            default: asm volatile("" : "+v"(gf[buf][4 % MT])); break;
         }
     };
     // At most n fragment reads (two LDS reads each) outstanding.
@@ -162,7 +168,8 @@ __device__ __forceinline__ void gemm_bf16_tn_body(const GemmBf16Args &p) {
             case 3: wait_lgkmcnt<6>(); break;
             case 4: wait_lgkmcnt<8>(); break;
             case 5: wait_lgkmcnt<10>(); break;
-            default: wait_lgkmcnt<12>(); break;
+            case 6: wait_lgkmcnt<12>(); break;
+            default: wait_lgkmcnt<14>(); break;
         }
     };
 
@@ -207,9 +214,9 @@ __device__ __forceinline__ void gemm_bf16_tn_body(const GemmBf16Args &p) {
             }
         };
 #endif
-        v16f acc[C::MT][C::NT];
+        v16f acc[MT][C::NT];
 #pragma unroll
-        for (int mt = 0; mt < C::MT; ++mt)
+        for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
             for (int nt = 0; nt < C::NT; ++nt)
 #pragma unroll
@@ -243,9 +250,9 @@ __device__ __forceinline__ void gemm_bf16_tn_body(const GemmBf16Args &p) {
                 int landed = 0;
                 if (kt < 50) SB_STAMP_AT(kk * 3 + 0, kt * 4 + 0);
 #pragma unroll
-                for (int idx = 0; idx < C::MT * C::NT; ++idx) {
+                for (int idx = 0; idx < MT * C::NT; ++idx) {
                     const int mt = idx / C::NT, nt = idx % C::NT;
-                    const int need = idx == 0 ? 2 : idx == 1 ? 3 : idx < 4 ? 4 : idx < 6 ? 5 : 6;
+                    const int need = idx == 0 ? 2 : idx == 1 ? 3 : 3 + idx / 2;
                     if (idx == 1 && kt < 50) SB_STAMP_AT(kk * 3 + 1, kt * 4 + 0);
                     if (need > landed) {
                         if (!has_next)
@@ -304,7 +311,7 @@ __device__ __forceinline__ void gemm_bf16_tn_body(const GemmBf16Args &p) {
             unsigned short *out = static_cast<unsigned short *>(p.out);
             unsigned char *epi = smem + S * C::STAGE_BYTES + wave * C::EPI_WAVE_BYTES;
 #pragma unroll
-            for (int mt = 0; mt < C::MT; ++mt) {
+            for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
                 for (int nt = 0; nt < C::NT; ++nt)
 #pragma unroll
@@ -330,7 +337,7 @@ __device__ __forceinline__ void gemm_bf16_tn_body(const GemmBf16Args &p) {
             // binary32: final result (one split) or this split's partial sums, straight from the registers.
             float *pout = p.splits > 1 ? p.partial + (int64_t)this_split * p.m * p.n : static_cast<float *>(p.out);
 #pragma unroll
-            for (int mt = 0; mt < C::MT; ++mt)
+            for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                 for (int nt = 0; nt < C::NT; ++nt)
 #pragma unroll
@@ -352,6 +359,19 @@ __device__ __forceinline__ void gemm_bf16_tn_body(const GemmBf16Args &p) {
         split = nsplit;
         KT = nKT;
     }
+}
+
+// The kernel body; the __global__ entry that calls it lives next to the launcher (a __global__ template that uses
+// device-only buffer builtins does not instantiate in the host pass).
+template <class C>
+__device__ __forceinline__ void gemm_bf16_tn_body(const GemmBf16Args &p) {
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform: what derives from it is scalar
+    if (C::MT_LOADER == 4)
+        gemm_bf16_tn_role<C, 4>(p, wave, (wave / C::WAVES_N) * C::WTM);
+    else if (wave < C::LOADERS)
+        gemm_bf16_tn_role<C, C::MT_LOADER>(p, wave, 0);
+    else
+        gemm_bf16_tn_role<C, 8 - C::MT_LOADER>(p, wave, C::MT_LOADER * 32);
 }
 
 }  // namespace sb
