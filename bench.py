@@ -21,14 +21,14 @@ if ROOT not in sys.path:
 
 PEAK = {"hbm_GBps": 8000.0, "int8_TOPs": 5000.0, "bf16_TFLOPs": 2500.0}
 
-# HBM-side bytes per step of each kernel group on the vit_h14 workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs of this script (FETCH_SIZE x2, WRITE_SIZE x1 after calibration against copy kernels of known size; summary and
-# commands in profiles/bench_vit_h14_hbm_traffic.md).  Not re-measured at run time; null for other workloads.
-TRAFFIC_BYTES_PER_STEP_VIT_H14 = {
-    "gemm_int8_dequant": 8 * (296.8e6 + 168.4e6),
-    "gemm_bf16_weight_grad": (2 * 1025.9e6 + 567.2e6 + 225.9e6) + (2 * 131.8e6 + 59.4e6 + 66.1e6)
-                             + (2 * 131.1e6 + 59.0e6 + 65.5e6) + (2 * 13.1e6 + 9.8e6 + 3.3e6),
-    "quantize_rowwise": 3 * (84.3e6 + 42.4e6) + (252.7e6 + 127.4e6) + 2 * (336.9e6 + 169.5e6) + 2 * (84.3e6 + 42.4e6),
+# HBM-side bytes per launch (mean over the launches of one step) of each kernel group on the vit_h14 workload, from
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script (FETCH_SIZE x2, WRITE_SIZE x1 after calibration against
+# copy kernels of known size; summary and commands in profiles/bench_vit_h14_hbm_traffic.md).  Not re-measured at run
+# time; null for other workloads.
+TRAFFIC_BYTES_PER_LAUNCH_VIT_H14 = {
+    "gemm_int8_dequant": 294.4e6 + 169.5e6,        # 8 launches per step; algorithmic mean 257.6e6
+    "gemm_bf16_weight_grad": 748.7e6 + 98.0e6,     # 4 launches per step, fp32 split-K partials included
+    "quantize_rowwise": 253.2e6,                   # 8 launches per step
 }
 
 
@@ -164,8 +164,8 @@ def main():
     roofline = {"kernel": dominant, "bound": kernels[dominant]["bound"], "achieved": kernels[dominant]["achieved"],
                 "peak": kernels[dominant]["peak"], "unit": kernels[dominant]["unit"],
                 "frac": kernels[dominant]["frac"],
-                "traffic": TRAFFIC_BYTES_PER_STEP_VIT_H14.get(dominant) if args.config == "vit_h14" else None,
-                "traffic_unit": "bytes per step (all launches of this kernel), HBM side, from profiles/"}
+                "traffic": TRAFFIC_BYTES_PER_LAUNCH_VIT_H14.get(dominant) if args.config == "vit_h14" else None,
+                "traffic_unit": "bytes per launch (mean over this kernel's launches of a step), HBM side, from profiles/"}
     op_sum = sum(k["ms_per_step"] for k in kernels.values())
     quant_ms = kernels["quantize_rowwise"]["ms_per_step"] + kernels["quantize_tensorwise"]["ms_per_step"]
 
