@@ -7,30 +7,37 @@
 //   * v_mfma_i32_32x32x32_i8.  The weight-side tile (bq rows) is the MFMA's first operand and the token-side
 //     tile (aq rows) its second, so a lane ends up owning ONE output row (lane % 32) and, per accumulator quad,
 //     four consecutive output columns: one row scale per lane, and packed bf16x4 leaves each quad.
-//   * 256x256 output tile per workgroup, eight waves with 128x64 wave tiles (4x2 MFMA blocks).  A persistent grid
-//     (one workgroup per compute unit) walks the tiles in an order that keeps the workgroups of one XCD
-//     (workgroup id % 8) on a compact patch of tiles, so its L2 sees each operand panel once.
+//   * 256x256 output tile per workgroup of eight waves, two per SIMD; a wave tile is 64 columns wide and 128 rows
+//     high (96 and 160 with the uneven split below).  A persistent grid (one workgroup per compute unit) walks the
+//     tiles in an order that keeps the workgroups of one XCD (workgroup id % 8) on a compact patch of tiles, so its
+//     L2 sees each operand panel once.
 //   * Operand tiles go HBM/L2 -> LDS with buffer_load_dwordx4 ... lds (no VGPR staging), STAGES deep.  One wave
 //     instruction fills 1 KiB of LDS linearly, so the bank-conflict-avoiding swizzle is applied on the GLOBAL side:
 //     LDS slot (row, p) holds 16-byte k-chunk p ^ f(row) of that row, f(row) = (row / (256/BK)) % (BK/16).  Rows past
 //     M (or N) lie beyond the buffer's num_records and read as zero; they only feed accumulators that are never
 //     stored.
+//   * One continuous stage pipeline: the stage ring runs across tile boundaries.  The load cursor stays STAGES
+//     stages ahead of the MFMAs, so a new tile's first stages are requested during the last k-tiles of the tile
+//     before it, and the epilogue needs no barrier of its own.
 //   * Wave roles.  A 1 KiB request occupies the CU's address/data path for ~18 cycles and the wave that issues it
 //     stalls meanwhile, MFMAs included; the 64 requests of a 64 KiB stage cost ~1200 cycles however they are dealt.
 //     With LOADERS = 4 only waves 0..3 issue them, all right after the stage hand-over barrier: waves w and w+4
 //     share a SIMD, so while a loader wave is stuck issuing its partner has the matrix pipe to itself, and the
-//     loader runs its MFMAs afterwards (best for long K).  With LOADERS = 8 every wave issues its share at the
-//     hand-over, which shortens the request burst at a tile boundary (best for short K, where that boundary
-//     weighs more).
+//     loader runs its MFMAs afterwards.  MT_LOADER = 3 evens out the two chains: the loader computes 3 of the 8
+//     32-row blocks of its wave column, its partner 5.  With LOADERS = 8 every wave issues its share at the hand-over.
 //   * MFMA operand fragments are double-buffered in registers, and the LDS reads of k-step j+1 are issued one at a
 //     time between the MFMAs of k-step j (also across the stage hand-over): an LDS read issued in the shadow of an
 //     MFMA costs no issue time.  The reads are inline asm so that the lgkmcnt waits can be counted; the compiler's
 //     own would drain the queue in front of every MFMA group.
 //   * Barriers are bare s_barrier instructions with explicit vmcnt / lgkmcnt waits; __syncthreads() would drain
-//     every outstanding global->LDS request.
-//   * The next tile's first STAGES stages are requested BEFORE the epilogue of the current tile.  The epilogue
-//     transposes the bf16 results through a wave-private, XOR-swizzled LDS patch and stores 16 bytes per lane,
-//     covering whole 128-byte row segments.
+//     every outstanding global->LDS request.  The vector-memory counter is one in-order counter for loads and
+//     stores, so every wave keeps books of what it issued after each stage's requests and waits for "at most that
+//     many outstanding".
+//   * The epilogue transposes the bf16 results through a wave-private, XOR-swizzled LDS patch and stores 16 bytes
+//     per lane, covering whole 128-byte row segments, with non-temporal buffer stores (the output must not evict
+//     the operand panels the other workgroups of the XCD are reading from L2).
+//   * SB_GEMM_TIMELINE (off in the library) compiles in cycle stamps at the code points of the main loop; the
+//     figures quoted above come from them.
 #pragma once
 #include "sb_common.h"
 #include <type_traits>
