@@ -91,6 +91,15 @@ def main():
             sb.backward_input(t["dy"], t["bufs"], dx=t["dx"])
             sb.backward_weight(t["dy"], t["x"], t["bufs"], dw=t["dw"])
 
+    def switchback_step_requant():
+        # Algorithm 1 as printed: the backward pass quantizes (and transposes) W again instead of keeping the codes.
+        for t in layers:
+            bufs = t["bufs"]
+            sb.forward(t["x"], t["w"], bufs=bufs, y=t["y"])
+            sb.quantize_tensorwise(t["w"], bufs.wq, bufs.wq_t, bufs.state_w, bufs.ws_fwd)
+            sb.backward_input(t["dy"], bufs, dx=t["dx"])
+            sb.backward_weight(t["dy"], t["x"], bufs, dw=t["dw"])
+
     def bf16_step():
         for t in layers:
             torch.matmul(t["x"], t["w"].t(), out=t["y"])
@@ -113,6 +122,7 @@ def main():
 
     sb_ms, sb_wall_ms = timed(switchback_step, args.steps, args.warmup)
     bf_ms, _ = timed(bf16_step, args.steps, args.warmup)
+    requant_ms, _ = timed(switchback_step_requant, max(3, args.steps // 2), 2)
 
     # ---- per-kernel times: the same kernels on the same shapes, one event pair around each launch group ------
     ops = {}  # name -> [total ms over reps, algorithmic work, unit kind]
@@ -216,6 +226,7 @@ def main():
         "bf16_linear_ms_per_step": round(bf_ms, 4),
         "bf16_linear_TFLOPs": round(flop_per_step / bf_ms / 1e9, 2),
         "wall_ms_per_step": round(sb_wall_ms, 4),
+        "ms_per_step_w_requantized_in_backward": round(requant_ms, 4),
         "roofline": roofline,
         "kernels": kernels,
         "sum_of_kernel_ms": round(op_sum, 4),

@@ -23,7 +23,10 @@
  *   - dequantization order: c = fl(state_W/127^2) once, r_i = fl(state_row[i]*c) per row,
  *     y = fl((float)acc * r_i) per element                      (the forward equation with dequantization);
  *   - Algorithm 1's backward dequantizes with the state of the quantized dY (its listing reuses the
- *     forward's name for it).
+ *     forward's name for it);
+ *   - the memory-efficient variant (SwitchBackM, the appendix algorithm that keeps only the int8 codes of X)
+ *     names a row-wise dequantization without printing it: taken as the inverse of the row-wise quantization
+ *     equation, x^_ij = fl(q_ij * fl(state_i / 127)), then rounded to bf16 (the layer's 16-bit type).
  */
 #include <math.h>
 #include <stdint.h>
@@ -106,6 +109,19 @@ void sbo_quantize_tensorwise(const uint16_t *w, int64_t rows, int64_t cols, int8
             q[i * cols + j] = v;
             if (q_t) q_t[j * rows + i] = v;
         }
+}
+
+/* Row-wise dequantization of the memory-efficient variant (SwitchBackM): the inverse of the row-wise quantization
+ * equation.  q [rows,cols] int8, state [rows] f32 (the row absmax) -> x_hat [rows,cols] bf16 patterns. */
+void sbo_dequantize_rowwise(const int8_t *q, const float *state, int64_t rows, int64_t cols, uint16_t *x_hat) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < rows; ++i) {
+        float step = state[i] / 127.0f; /* fl(state_i / 127): what one code unit is worth in this row */
+        for (int64_t j = 0; j < cols; ++j) {
+            float v = (float)q[i * cols + j] * step; /* fl(q * step); (float)q is exact */
+            x_hat[i * cols + j] = f32_to_bf16_rne(v);
+        }
+    }
 }
 
 /* ---- integer matmul ("int8 matmul" under-brace of the forward equation) -------------------------------- */

@@ -78,6 +78,18 @@ def quantize_tensorwise(w):
     return q, q_t, state[0]
 
 
+def dequantize_rowwise(q, state):
+    """Row-wise dequantization of SwitchBackM (inverse of the row-wise quantization equation): bf16 patterns
+    of fl(q * fl(state/127)), uint16 [r,c]."""
+    q = np.ascontiguousarray(q, dtype=np.int8)
+    state = np.ascontiguousarray(state, dtype=np.float32)
+    r, c = q.shape
+    assert state.shape == (r,)
+    out = np.empty((r, c), np.uint16)
+    _load().sbo_dequantize_rowwise(_p(q), _p(state), _i64(r), _i64(c), _p(out))
+    return out
+
+
 def matmul_int8(a, b):
     """acc = a b^T exactly, a [M,K], b [N,K] int8 -> int32 [M,N].  Raises if a sum leaves int32."""
     a = np.ascontiguousarray(a)
@@ -143,6 +155,15 @@ def backward_input(dy, wq_t, state_w):
     acc = matmul_int8(gq, wq_t)
     dx32 = dequantize(acc, state_g, state_w)
     return dict(gq=gq, state_g=state_g, acc=acc, dx32=dx32, dx_bf16=round_to_bf16(dx32))
+
+
+def backward_weight_m(dy, xq, state_x):
+    """Weight gradient of SwitchBackM: X is first rebuilt from its int8 codes (row-wise dequantization), then the
+    16-bit matmul as in Algorithm 1."""
+    x_hat = dequantize_rowwise(xq, state_x)
+    out = backward_weight(dy, x_hat)
+    out["x_hat"] = x_hat
+    return out
 
 
 def backward_weight(dy, x):

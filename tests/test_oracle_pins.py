@@ -343,3 +343,69 @@ def test_all_zero_row_yields_zero_output(oracle):
     f = oracle.forward(x, w)
     assert not f["y32"][5].any() and not (f["y_bf16"][5] & 0x7FFF).any()
     assert f["y32"][4].any()
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# SwitchBackM (the appendix variant that keeps only the int8 codes of X): row-wise dequantization
+# ---------------------------------------------------------------------------------------------------------------
+
+def test_rowwise_dequantization_inverts_the_quantizer(oracle):
+    """x^ = q * state/127 must bring every element back to within half a quantization step (the row-wise
+    quantization equation read backwards) plus the bf16 rounding of the result; integer rows with absmax 127 come
+    back exactly; the sign and power-of-two symmetries of the quantizer carry over."""
+    rng = np.random.default_rng(31)
+    x = rand_bf16(rng, (40, 96), 3.0)
+    q, s = oracle.quantize_rowwise(x)
+    xh = oracle.dequantize_rowwise(q, s)
+    xv, hv, sv = f32(x).astype(np.float64), f32(xh).astype(np.float64), s.astype(np.float64)[:, None]
+    half_step = sv / 254.0 * (1 + 2.0 ** -14)
+    assert np.all(np.abs(xv - hv) <= half_step + np.abs(hv) * 2.0 ** -8)
+    # the arg-absmax element carries code +-127 and must come back to the absmax within one bf16 rounding
+    top = np.abs(xv).argmax(axis=1)
+    rows = np.arange(40)
+    assert np.all(np.abs(np.abs(hv[rows, top]) - sv[:, 0]) <= sv[:, 0] * 2.0 ** -8)
+    # fixed points: integers in [-127, 127] with a +-127 in the row (scale exactly 1)
+    xi = rng.integers(-127, 128, size=(6, 32)).astype(np.float32)
+    xi[:, 0] = 127
+    qi, si = oracle.quantize_rowwise(bf(xi))
+    np.testing.assert_array_equal(f32(oracle.dequantize_rowwise(qi, si)), xi)   # (such integers are bf16-exact)
+    # symmetries
+    np.testing.assert_array_equal(f32(oracle.dequantize_rowwise(-q, s)), -f32(xh))
+    np.testing.assert_array_equal(f32(oracle.dequantize_rowwise(q, s * 8.0)), f32(xh) * 8.0)
+    # a row whose state is 0 (all-zero or overflowing scale) comes back as zeros
+    z = oracle.dequantize_rowwise(np.zeros((2, 16), np.int8), np.zeros(2, np.float32))
+    assert not (z & 0x7FFF).any()
+
+
+def test_rowwise_dequantization_matches_independent_arithmetic(oracle):
+    """Element by element against NumPy's correctly rounded binary32 divide and multiply and torch's bf16 cast
+    (none of it the oracle's own code), and against exact rationals on a few elements."""
+    rng = np.random.default_rng(32)
+    q = rng.integers(-127, 128, size=(24, 80)).astype(np.int8)
+    s = f32(rand_bf16(rng, (24,), 5.0)).astype(np.float32)
+    s = np.abs(s) + np.float32(0.01)
+    got = oracle.dequantize_rowwise(q, s)
+    step = (s / np.float32(127.0)).astype(np.float32)                       # fl(s / 127)
+    v = (q.astype(np.float32) * step[:, None]).astype(np.float32)           # fl(q * step)
+    want = torch.from_numpy(v).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    np.testing.assert_array_equal(got, want)
+    for i, j in [(0, 0), (3, 17), (23, 79)]:
+        exact_step = Fraction(float(s[i])) / 127
+        assert abs(Fraction(float(step[i])) - exact_step) <= abs(exact_step) * Fraction(1, 2 ** 24)
+        exact_v = Fraction(int(q[i, j])) * Fraction(float(step[i]))
+        assert abs(Fraction(float(v[i, j])) - exact_v) <= abs(exact_v) * Fraction(1, 2 ** 24)
+
+
+def test_switchback_m_weight_gradient_stays_within_the_quantization_bound(oracle):
+    """dW of the memory-efficient variant differs from Algorithm 1's only through x^ - x, which is bounded per row:
+    |dW_M - dW|[j,k] <= sum_i |dY_ij| * (s_i/254 * (1 + 2^-14) + |x^_ik| * 2^-8)."""
+    d = I.make_layer_inputs("tiny")
+    dy, x = d["dy"][:160, :40], d["x"][:160, :56]
+    xq, sx = oracle.quantize_rowwise(x)
+    rm = oracle.backward_weight_m(dy, xq, sx)
+    r = oracle.backward_weight(dy, x)
+    gv = np.abs(f32(dy).astype(np.float64))
+    per_row = sx.astype(np.float64)[:, None] / 254.0 * (1 + 2.0 ** -14) + np.abs(f32(rm["x_hat"]).astype(np.float64)) * 2.0 ** -8
+    bound = gv.T @ per_row
+    assert np.all(np.abs(rm["dw64"] - r["dw64"]) <= bound * (1 + 1e-9))
+    assert np.abs(rm["dw64"] - r["dw64"]).max() > 0          # the variant is not a no-op
