@@ -100,6 +100,17 @@ def main():
             sb.backward_input(t["dy"], bufs, dx=t["dx"])
             sb.backward_weight(t["dy"], t["x"], bufs, dw=t["dw"])
 
+    x_hat = torch.empty((max(L.b * L.n for L in cfg.layers),), dtype=torch.bfloat16, device=dev)
+
+    def switchback_m_step():
+        # The memory-efficient variant (SwitchBackM): only X_int8 and state_X survive the forward pass; the weight
+        # gradient rebuilds X by row-wise dequantization.
+        for t in layers:
+            L = t["L"]
+            sb.forward(t["x"], t["w"], bufs=t["bufs"], y=t["y"])
+            sb.backward_input(t["dy"], t["bufs"], dx=t["dx"])
+            sb.backward_weight_m(t["dy"], t["bufs"], x_hat=x_hat[: L.b * L.n].view(L.b, L.n), dw=t["dw"])
+
     def bf16_step():
         for t in layers:
             torch.matmul(t["x"], t["w"].t(), out=t["y"])
@@ -123,6 +134,7 @@ def main():
     sb_ms, sb_wall_ms = timed(switchback_step, args.steps, args.warmup)
     bf_ms, _ = timed(bf16_step, args.steps, args.warmup)
     requant_ms, _ = timed(switchback_step_requant, max(3, args.steps // 2), 2)
+    variant_m_ms, _ = timed(switchback_m_step, max(3, args.steps // 2), 2)
 
     # ---- per-kernel times: the same kernels on the same shapes, one event pair around each launch group ------
     ops = {}  # name -> [total ms over reps, algorithmic work, unit kind]
@@ -149,6 +161,9 @@ def main():
                 b * n * 3.0 + 4.0 * b, "bytes", reps)
         time_op("quantize_rowwise", lambda: sb.quantize_rowwise(t["dy"], bufs.gq, bufs.state_g),
                 b * m * 3.0 + 4.0 * b, "bytes", reps)
+        time_op("dequantize_rowwise (SwitchBackM only)",
+                lambda: sb.dequantize_rowwise(bufs.xq, bufs.state_x, out=x_hat[: b * n].view(b, n)),
+                b * n * 3.0 + 4.0 * b, "bytes", reps)
         time_op("quantize_tensorwise",
                 lambda: sb.quantize_tensorwise(t["w"], bufs.wq, bufs.wq_t, bufs.state_w, bufs.ws_fwd),
                 m * n * 6.0, "bytes", reps)
@@ -170,13 +185,13 @@ def main():
             peak = PEAK["int8_TOPs"] if kind == "int8" else PEAK["bf16_TFLOPs"]
         kernels[name] = {"ms_per_step": round(ms, 4), "bound": bound, "achieved": round(ach, 1), "peak": peak,
                          "unit": unit, "frac": round(ach / peak, 4)}
-    dominant = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
+    dominant = max((k for k in kernels if "SwitchBackM" not in k), key=lambda k: kernels[k]["ms_per_step"])
     roofline = {"kernel": dominant, "bound": kernels[dominant]["bound"], "achieved": kernels[dominant]["achieved"],
                 "peak": kernels[dominant]["peak"], "unit": kernels[dominant]["unit"],
                 "frac": kernels[dominant]["frac"],
                 "traffic": TRAFFIC_BYTES_PER_LAUNCH_VIT_H14.get(dominant) if args.config == "vit_h14" else None,
                 "traffic_unit": "bytes per launch (mean over this kernel's launches of a step), HBM side, from profiles/"}
-    op_sum = sum(k["ms_per_step"] for k in kernels.values())
+    op_sum = sum(v["ms_per_step"] for k, v in kernels.items() if "SwitchBackM" not in k)
     quant_ms = kernels["quantize_rowwise"]["ms_per_step"] + kernels["quantize_tensorwise"]["ms_per_step"]
 
     if args.copy_calibration:
@@ -227,6 +242,7 @@ def main():
         "bf16_linear_TFLOPs": round(flop_per_step / bf_ms / 1e9, 2),
         "wall_ms_per_step": round(sb_wall_ms, 4),
         "ms_per_step_w_requantized_in_backward": round(requant_ms, 4),
+        "ms_per_step_switchback_m": round(variant_m_ms, 4),
         "roofline": roofline,
         "kernels": kernels,
         "sum_of_kernel_ms": round(op_sum, 4),

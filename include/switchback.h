@@ -110,6 +110,23 @@ int switchback_backward_input(const void *dy_bf16, const sb_saved *saved, int64_
 int switchback_backward_weight(const void *dy_bf16, const void *x_bf16, int64_t b, int64_t n, int64_t m,
                                void *dw, sb_dtype dw_dtype, void *ws, size_t ws_bytes, void *stream);
 
+/* The memory-efficient variant SwitchBackM (the appendix algorithm that keeps only X_int8 and state_X of the input
+ * for the backward pass instead of X in 16 bit).  Its forward pass and input gradient are those of Algorithm 1
+ * (switchback_forward fills saved->xq and saved->state_x); its weight gradient first rebuilds X:
+ *
+ * switchback_dequantize_rowwise: x^[i,j] = q[i,j] * state[i] / 127, the row-wise quantization equation read
+ * backwards, evaluated in binary32 as step_i = state[i] / 127 (correctly rounded), fl((float)q * step_i), then
+ * rounded to nearest-even bf16.  q [rows,cols] int8, state [rows] f32 in; x_bf16 [rows,cols] out.  cols % 8 == 0.
+ *
+ * switchback_backward_weight_m: dW = dY^T X^ with X^ = dequantize_rowwise(saved->xq, saved->state_x) written to
+ * x_hat_bf16 [b,n] (caller-provided scratch, may be reused once the stream has passed the call); then exactly
+ * switchback_backward_weight on (dy, x_hat).  ws: SB_OP_BACKWARD_WEIGHT workspace. */
+int switchback_dequantize_rowwise(const int8_t *q, const float *state, int64_t rows, int64_t cols, void *x_bf16,
+                                  void *stream);
+int switchback_backward_weight_m(const void *dy_bf16, const sb_saved *saved, int64_t b, int64_t n, int64_t m,
+                                 void *x_hat_bf16, void *dw, sb_dtype dw_dtype, void *ws, size_t ws_bytes,
+                                 void *stream);
+
 /* Bytes of device workspace `op` needs for a layer of this shape (0 if none).  Shape arguments an op does not
  * use are ignored (for SB_OP_QUANTIZE_TENSORWISE pass rows as m and cols as n). */
 size_t switchback_workspace_bytes(int op, int64_t b, int64_t n, int64_t m);

@@ -233,7 +233,40 @@ __global__ __launch_bounds__(256) void quantize_tensorwise_kernel(const v4u *__r
     }
 }
 
+// Row-wise dequantization of the memory-efficient variant (SwitchBackM, the appendix algorithm that saves only the
+// int8 codes of X): x^[i,j] = bf16(fl((float)q[i,j] * fl(state[i] / 127))), the row-wise quantization equation read
+// backwards.  One wavefront per row, 8 codes (8 bytes in, 16 bytes out) per lane and step.
+__global__ __launch_bounds__(256) void dequantize_rowwise_kernel(const v2u *__restrict__ q, const float *__restrict__ state,
+                                                                 int64_t rows, int chunks, v4u *__restrict__ x_hat) {
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const int lane = threadIdx.x & 63;
+    const float step = state[row] / 127.0f;  // correctly rounded divide
+    const v2u *qr = q + row * chunks;
+    v4u *xr = x_hat + row * chunks;
+    for (int c = lane; c < chunks; c += 64) {
+        const v2u w = __builtin_nontemporal_load(qr + c);
+        v4f lo, hi;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            lo[e] = (float)(int)(signed char)(w.x >> (8 * e)) * step;
+            hi[e] = (float)(int)(signed char)(w.y >> (8 * e)) * step;
+        }
+        const v4bf a = __builtin_convertvector(lo, v4bf), b = __builtin_convertvector(hi, v4bf);
+        const v2u pa = __builtin_bit_cast(v2u, a), pb = __builtin_bit_cast(v2u, b);
+        xr[c] = v4u{pa.x, pa.y, pb.x, pb.y};
+    }
+}
+
 }  // namespace
+
+hipError_t launch_dequantize_rowwise(const int8_t *q, const float *state, int64_t rows, int64_t cols, void *x_hat,
+                                     hipStream_t stream) {
+    if (rows == 0) return hipSuccess;
+    dequantize_rowwise_kernel<<<(unsigned int)((rows + 3) / 4), 256, 0, stream>>>(
+        reinterpret_cast<const v2u *>(q), state, rows, (int)(cols / 8), static_cast<v4u *>(x_hat));
+    return hipGetLastError();
+}
 
 hipError_t launch_quantize_rowwise(const void *x, int64_t rows, int64_t cols, int8_t *q, float *state,
                                    hipStream_t stream) {

@@ -31,6 +31,8 @@ __device__ __forceinline__ float bf16_bits_to_float(unsigned int bits16) { retur
 // Launchers (each validates nothing: the C-ABI layer has already checked shapes and pointers).
 hipError_t launch_quantize_rowwise(const void *x, int64_t rows, int64_t cols, int8_t *q, float *state,
                                    hipStream_t stream);
+hipError_t launch_dequantize_rowwise(const int8_t *q, const float *state, int64_t rows, int64_t cols, void *x_hat,
+                                     hipStream_t stream);
 hipError_t launch_quantize_tensorwise(const void *w, int64_t rows, int64_t cols, int8_t *q, int8_t *q_t,
                                       float *state, unsigned int *partials, hipStream_t stream);
 hipError_t launch_gemm_i8_dequant(const int8_t *aq, const float *state_row, const int8_t *bq,

@@ -34,6 +34,15 @@ int switchback_quantize_rowwise(const void *x_bf16, int64_t rows, int64_t cols, 
     return from_hip(sb::launch_quantize_rowwise(x_bf16, rows, cols, q, state, static_cast<hipStream_t>(stream)));
 }
 
+int switchback_dequantize_rowwise(const int8_t *q, const float *state, int64_t rows, int64_t cols, void *x_bf16,
+                                  void *stream) {
+    if (rows < 0 || cols <= 0) return SB_INVALID_ARG;
+    if (cols % 8 || cols > 65536 || rows > (int64_t)1 << 30) return SB_UNSUPPORTED_SHAPE;
+    if (rows == 0) return SB_OK;
+    if (!ok_ptr(q) || !ok_ptr(x_bf16) || state == nullptr) return SB_INVALID_ARG;
+    return from_hip(sb::launch_dequantize_rowwise(q, state, rows, cols, x_bf16, static_cast<hipStream_t>(stream)));
+}
+
 int switchback_quantize_tensorwise(const void *w_bf16, int64_t rows, int64_t cols, int8_t *q, int8_t *q_t,
                                    float *state, void *ws, size_t ws_bytes, void *stream) {
     if (rows <= 0 || cols <= 0) return SB_INVALID_ARG;
@@ -116,6 +125,28 @@ int switchback_backward_weight(const void *dy_bf16, const void *x_bf16, int64_t 
     // Algorithm 1, backward: W_gradient = 16-bit matmul of dY^T and X (b == 0 gives an all-zero gradient).
     return from_hip(sb::launch_gemm_bf16_tn(dy_bf16, x_bf16, b, n, m, dw, dw_dtype, ws,
                                             static_cast<hipStream_t>(stream)));
+}
+
+int switchback_backward_weight_m(const void *dy_bf16, const sb_saved *saved, int64_t b, int64_t n, int64_t m,
+                                 void *x_hat_bf16, void *dw, sb_dtype dw_dtype, void *ws, size_t ws_bytes,
+                                 void *stream) {
+    int st = layer_shape_status(b, n, m);
+    if (st != SB_OK) return st;
+    if (saved == nullptr) return SB_INVALID_ARG;
+    if (b > 0 && (!ok_ptr(saved->xq) || saved->state_x == nullptr || !ok_ptr(x_hat_bf16))) return SB_INVALID_ARG;
+    // SwitchBackM backward: X = row-wise dequantize(X_int8, state_X), then the 16-bit matmul of Algorithm 1.  The
+    // weight-gradient call validates the remaining arguments before anything is enqueued.
+    if (dw_dtype != SB_BF16 && dw_dtype != SB_F32) return SB_INVALID_ARG;
+    if (!ok_ptr(dw) || (b > 0 && !ok_ptr(dy_bf16))) return SB_INVALID_ARG;
+    const size_t need = switchback_workspace_bytes(SB_OP_BACKWARD_WEIGHT, b, n, m);
+    if (need > 0 && (ws == nullptr || !aligned16(ws))) return SB_INVALID_ARG;
+    if (ws_bytes < need) return SB_WORKSPACE_TOO_SMALL;
+    if (b > 0) {
+        hipError_t e = sb::launch_dequantize_rowwise(saved->xq, saved->state_x, b, n, x_hat_bf16,
+                                                     static_cast<hipStream_t>(stream));
+        if (e != hipSuccess) return SB_HIP_ERROR;
+    }
+    return switchback_backward_weight(dy_bf16, x_hat_bf16, b, n, m, dw, dw_dtype, ws, ws_bytes, stream);
 }
 
 size_t switchback_workspace_bytes(int op, int64_t b, int64_t n, int64_t m) {

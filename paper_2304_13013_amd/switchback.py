@@ -49,12 +49,15 @@ def load_library():
     lib.switchback_forward.argtypes = [vp, vp, i64, i64, i64, vp, ci, ctypes.POINTER(SbSaved), vp, sz, vp]
     lib.switchback_backward_input.argtypes = [vp, ctypes.POINTER(SbSaved), i64, i64, i64, vp, ci, vp, vp, vp]
     lib.switchback_backward_weight.argtypes = [vp, vp, i64, i64, i64, vp, ci, vp, sz, vp]
+    lib.switchback_dequantize_rowwise.argtypes = [vp, vp, i64, i64, vp, vp]
+    lib.switchback_backward_weight_m.argtypes = [vp, ctypes.POINTER(SbSaved), i64, i64, i64, vp, vp, ci, vp, sz, vp]
     lib.switchback_workspace_bytes.argtypes = [ci, i64, i64, i64]
     lib.switchback_workspace_bytes.restype = sz
     lib.switchback_status_string.argtypes = [ci]
     lib.switchback_status_string.restype = ctypes.c_char_p
     for name in ("switchback_quantize_rowwise", "switchback_quantize_tensorwise", "switchback_matmul_int8_dequant",
-                 "switchback_forward", "switchback_backward_input", "switchback_backward_weight"):
+                 "switchback_forward", "switchback_backward_input", "switchback_backward_weight",
+                 "switchback_dequantize_rowwise", "switchback_backward_weight_m"):
         getattr(lib, name).restype = ci
     _lib = lib
     return lib
@@ -102,6 +105,16 @@ def quantize_rowwise(x, q=None, state=None):
     _check(lib.switchback_quantize_rowwise(xp, rows, cols, _dev(q, torch.int8), _dev(state, torch.float32),
                                            _stream()))
     return q, state
+
+
+def dequantize_rowwise(q, state, out=None):
+    """Row-wise dequantization of SwitchBackM: bf16 [rows, cols] = q * state / 127."""
+    lib = load_library()
+    rows, cols = q.shape
+    out = torch.empty((rows, cols), dtype=torch.bfloat16, device=q.device) if out is None else out
+    _check(lib.switchback_dequantize_rowwise(_dev(q, torch.int8, 2), _dev(state, torch.float32), rows, cols,
+                                             _dev(out, torch.bfloat16, 2), _stream()))
+    return out
 
 
 def quantize_tensorwise(w, q=None, q_t=None, state=None, ws=None, transpose=True):
@@ -192,3 +205,17 @@ def backward_weight(dy, x, bufs=None, dw=None, dw_dtype=torch.bfloat16):
                                           _dev(dw, dw_dtype, 2), _SB_DTYPE[dw_dtype], _ptr(ws), ws.numel(),
                                           _stream()))
     return dw
+
+
+def backward_weight_m(dy, bufs, x_hat=None, dw=None, dw_dtype=torch.bfloat16):
+    """SwitchBackM weight gradient: X is rebuilt from bufs.xq / bufs.state_x (filled by forward) into x_hat, then
+    dW = dY^T X^.  Returns (dw [m,n], x_hat [b,n])."""
+    lib = load_library()
+    b, m = dy.shape
+    n = bufs.n
+    x_hat = torch.empty((b, n), dtype=torch.bfloat16, device=dy.device) if x_hat is None else x_hat
+    dw = torch.empty((m, n), dtype=dw_dtype, device=dy.device) if dw is None else dw
+    _check(lib.switchback_backward_weight_m(_dev(dy, torch.bfloat16, 2), ctypes.byref(bufs.saved), b, n, m,
+                                            _dev(x_hat, torch.bfloat16, 2), _dev(dw, dw_dtype, 2),
+                                            _SB_DTYPE[dw_dtype], _ptr(bufs.ws_dw), bufs.ws_dw.numel(), _stream()))
+    return dw, x_hat

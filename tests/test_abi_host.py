@@ -77,6 +77,11 @@ def test_bad_arguments_are_rejected_before_launch(lib):
     assert lib.switchback_backward_input(fake, sp, 8, 64, 96, fake, 0, fake, fake, null) == SHAPE
     assert lib.switchback_backward_input(null, sp, 8, 64, 64, fake, 0, fake, fake, null) == INVALID
     assert lib.switchback_backward_input(null, sp, 0, 64, 64, null, 0, null, null, null) == 0   # b = 0
+    assert lib.switchback_dequantize_rowwise(fake, fake, 4, 60, fake, null) == SHAPE
+    assert lib.switchback_dequantize_rowwise(fake, null, 4, 64, fake, null) == INVALID
+    assert lib.switchback_dequantize_rowwise(null, null, 0, 64, null, null) == 0          # empty input: no-op
+    assert lib.switchback_backward_weight_m(fake, sp, 8, 64, 64, null, fake, 0, fake, 1 << 30, null) == INVALID
+    assert lib.switchback_backward_weight_m(fake, sp, 32896, 1280, 1280, fake, fake, 0, fake, 64, null) == WS
     assert lib.switchback_backward_weight(fake, fake, 8, 64, 64, fake, 2, fake, 1 << 30, null) == INVALID
     assert lib.switchback_backward_weight(fake, fake, 32896, 1280, 1280, fake, 0, fake, 64, null) == WS
     assert lib.switchback_backward_weight(fake, fake, 8, 64, 64, null, 0, fake, 1 << 30, null) == INVALID

@@ -140,6 +140,53 @@ def test_dequantized_product(oracle, M, N, K):
 
 
 # ---------------------------------------------------------------------------------------------------------------
+# SwitchBackM: row-wise dequantization (bit-exact) and the weight gradient built on it
+# ---------------------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("rows,cols", [(512, 256), (1, 8), (3, 64), (37, 520), (257, 1280), (129, 5120), (5, 16392),
+                                       (2, 65536)])
+def test_dequantize_rowwise(oracle, rows, cols):
+    rng = np.random.default_rng(rows * 17 + cols)
+    q = rng.integers(-127, 128, size=(rows, cols)).astype(np.int8)
+    s = np.abs(rng.standard_normal(rows)).astype(np.float32) * np.float32(3.0)
+    s[0] = 0.0                                                 # a zero row's state
+    if rows > 2:
+        s[1], s[2] = np.float32(254.0), np.float32(2.0 ** -120)
+    got = sb.dequantize_rowwise(torch.from_numpy(q).to(DEV), torch.from_numpy(s).to(DEV))
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(bits_of(got), oracle.dequantize_rowwise(q, s))
+
+
+def test_dequantize_rowwise_empty():
+    q = torch.empty((0, 64), dtype=torch.int8, device=DEV)
+    out = sb.dequantize_rowwise(q, torch.empty((0,), dtype=torch.float32, device=DEV))
+    assert out.shape == (0, 64)
+
+
+@pytest.mark.parametrize("shape", ["tiny", (197, 320, 64), (1000, 64, 256)])
+def test_switchback_m_weight_gradient(oracle, shape):
+    if shape == "tiny":
+        d = I.make_layer_inputs("tiny")
+        I.plant_edge_rows(d["x"])
+    else:
+        b, n, m = shape
+        rng = np.random.default_rng(b + n + m)
+        d = dict(x=rand_bf16(rng, (b, n)), w=rand_bf16(rng, (m, n), n ** -0.5), dy=rand_bf16(rng, (b, m), 0.1))
+    x, w, dy = to_dev(d["x"]), to_dev(d["w"]), to_dev(d["dy"])
+    _, bufs = sb.forward(x, w)                                 # fills xq, state_x: all the variant keeps of X
+    dw32, x_hat = sb.backward_weight_m(dy, bufs, dw_dtype=torch.float32)
+    dwbf, _ = sb.backward_weight_m(dy, bufs, dw_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    xq, sx = oracle.quantize_rowwise(d["x"])
+    h = oracle.backward_weight_m(d["dy"], xq, sx)
+    np.testing.assert_array_equal(bits_of(x_hat), h["x_hat"])
+    rms = float(np.sqrt((h["dw64"] ** 2).mean()))
+    got = host(dw32)
+    assert np.abs(got.astype(np.float64) - h["dw64"]).max() <= 1e-2 * rms
+    np.testing.assert_array_equal(bits_of(dwbf), oracle.round_to_bf16(got))
+
+
+# ---------------------------------------------------------------------------------------------------------------
 # the layer: tiny config, everything compared in full
 # ---------------------------------------------------------------------------------------------------------------
 
@@ -271,3 +318,12 @@ def test_layer_full_size_sampled(oracle, config, layer):
     rms = float(np.sqrt((dw_ref ** 2).mean()))
     got = host(dw32[torch.from_numpy(jrows).to(DEV)]).astype(np.float64)
     assert np.abs(got - dw_ref).max() <= 1e-2 * rms
+
+    # SwitchBackM: the dequantized X in full (bit-exact), its weight gradient on the same sampled rows
+    dwm, x_hat = sb.backward_weight_m(dy, bufs, dw_dtype=torch.float32)
+    torch.cuda.synchronize()
+    xh = oracle.dequantize_rowwise(xq, sx)
+    np.testing.assert_array_equal(bits_of(x_hat), xh)
+    dwm_ref = oracle.weight_grad(np.ascontiguousarray(d["dy"][:, jrows]), xh)
+    got = host(dwm[torch.from_numpy(jrows).to(DEV)]).astype(np.float64)
+    assert np.abs(got - dwm_ref).max() <= 1e-2 * float(np.sqrt((dwm_ref ** 2).mean()))
