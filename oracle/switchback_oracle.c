@@ -26,7 +26,11 @@
  *     forward's name for it);
  *   - the memory-efficient variant (SwitchBackM, the appendix algorithm that keeps only the int8 codes of X)
  *     names a row-wise dequantization without printing it: taken as the inverse of the row-wise quantization
- *     equation, x^_ij = fl(q_ij * fl(state_i / 127)), then rounded to bf16 (the layer's 16-bit type).
+ *     equation, x^_ij = fl(q_ij * fl(state_i / 127)), then rounded to bf16 (the layer's 16-bit type);
+ *   - the variant with row-wise and column-wise weight quantization (SwitchBackQ) gives its forward pass as
+ *     1/127^2 * state_row(X) state_row(W)^T * (int8 matmul) without an order of evaluation: taken as the order of
+ *     the tensor-wise case with the weight state now per output column, c_j = fl(state_W[j]/127^2) once per
+ *     column, then fl(state_row[i] * c_j), then fl((float)acc * that) per element.
  */
 #include <math.h>
 #include <stdint.h>
@@ -158,6 +162,21 @@ void sbo_dequantize(const int32_t *acc, int64_t M, int64_t N, const float *state
                     (double)acc[i * N + j] * (double)state_row[i] * (double)state_tensor / 16129.0;
         }
     }
+}
+
+/* SwitchBackQ: both operands carry one state per row of their code matrix, so the product has a row state and a
+ * column state: y32[i,j] = fl((float)acc[i,j] * fl(state_row[i] * fl(state_col[j]/16129))); y64 in binary64. */
+void sbo_dequantize_rowcol(const int32_t *acc, int64_t M, int64_t N, const float *state_row, const float *state_col,
+                           float *y32, double *y64) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M; ++i)
+        for (int64_t j = 0; j < N; ++j) {
+            float c = state_col[j] / 16129.0f; /* fl(state_col[j] / 127^2) */
+            float r = state_row[i] * c;        /* fl(state_row[i] * c) */
+            y32[i * N + j] = (float)acc[i * N + j] * r;
+            if (y64)
+                y64[i * N + j] = (double)acc[i * N + j] * (double)state_row[i] * (double)state_col[j] / 16129.0;
+        }
 }
 
 void sbo_round_to_bf16(const float *y, int64_t count, uint16_t *out) {

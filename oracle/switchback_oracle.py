@@ -117,6 +117,48 @@ def dequantize(acc, state_row, state_tensor, want_f64=False):
     return (y32, y64) if want_f64 else y32
 
 
+def dequantize_rowcol(acc, state_row, state_col, want_f64=False):
+    """SwitchBackQ dequantization: y = acc * state_row[i] * state_col[j] / 127^2 (binary32, column constant first)."""
+    acc = np.ascontiguousarray(acc, dtype=np.int32)
+    M, N = acc.shape
+    state_row = np.ascontiguousarray(state_row, dtype=np.float32)
+    state_col = np.ascontiguousarray(state_col, dtype=np.float32)
+    assert state_row.shape == (M,) and state_col.shape == (N,)
+    y32 = np.empty((M, N), np.float32)
+    y64 = np.empty((M, N), np.float64) if want_f64 else None
+    _load().sbo_dequantize_rowcol(_p(acc), _i64(M), _i64(N), _p(state_row), _p(state_col), _p(y32),
+                                  _p(y64) if want_f64 else None)
+    return (y32, y64) if want_f64 else y32
+
+
+def quantize_colwise_transpose(w):
+    """SwitchBackQ's column-wise quantization fused with a transpose: every column of w [rows, cols] gets its own
+    absmax; the codes come out transposed, [cols, rows].  By definition this is the row-wise quantization of the
+    transposed matrix.  Returns (q_t int8 [cols, rows], state f32 [cols])."""
+    w = _bf16(w)
+    return quantize_rowwise(np.ascontiguousarray(w.T))
+
+
+def forward_q(x, w):
+    """SwitchBackQ forward: row-wise quantization of X and of W (one state per output feature)."""
+    xq, state_x = quantize_rowwise(x)
+    wq, state_w = quantize_rowwise(w)
+    acc = matmul_int8(xq, wq)
+    y32 = dequantize_rowcol(acc, state_x, state_w)
+    return dict(xq=xq, state_x=state_x, wq=wq, state_w=state_w, acc=acc, y32=y32, y_bf16=round_to_bf16(y32))
+
+
+def backward_input_q(dy, w):
+    """SwitchBackQ input gradient: row-wise quantization of dY, column-wise (transposed) quantization of W, so the
+    contraction over m has one state per token and one per input feature."""
+    gq, state_g = quantize_rowwise(dy)
+    wq_t, state_wc = quantize_colwise_transpose(w)
+    acc = matmul_int8(gq, wq_t)
+    dx32 = dequantize_rowcol(acc, state_g, state_wc)
+    return dict(gq=gq, state_g=state_g, wq_t=wq_t, state_wc=state_wc, acc=acc, dx32=dx32,
+                dx_bf16=round_to_bf16(dx32))
+
+
 def round_to_bf16(y32):
     """binary32 -> bf16 bit patterns, round-to-nearest-even."""
     y32 = np.ascontiguousarray(y32, dtype=np.float32)

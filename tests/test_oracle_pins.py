@@ -409,3 +409,70 @@ def test_switchback_m_weight_gradient_stays_within_the_quantization_bound(oracle
     bound = gv.T @ per_row
     assert np.all(np.abs(rm["dw64"] - r["dw64"]) <= bound * (1 + 1e-9))
     assert np.abs(rm["dw64"] - r["dw64"]).max() > 0          # the variant is not a no-op
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# SwitchBackQ (row-wise and column-wise weight quantization)
+# ---------------------------------------------------------------------------------------------------------------
+
+def test_rowcol_dequantization(oracle):
+    """With every column state equal it must be the tensor-wise dequantization bit for bit; in general it must be the
+    binary64 product acc * s_i * s_j / 127^2 within the three binary32 roundings it is built from."""
+    rng = np.random.default_rng(41)
+    acc = rng.integers(-2 ** 22, 2 ** 22, size=(20, 48)).astype(np.int32)
+    srow = np.abs(rng.standard_normal(20)).astype(np.float32) + np.float32(0.1)
+    same = np.full(48, 0.734375, np.float32)
+    np.testing.assert_array_equal(oracle.dequantize_rowcol(acc, srow, same), oracle.dequantize(acc, srow, same[0]))
+    scol = np.abs(rng.standard_normal(48)).astype(np.float32) + np.float32(0.05)
+    y32, y64 = oracle.dequantize_rowcol(acc, srow, scol, want_f64=True)
+    ref = acc.astype(np.float64) * srow.astype(np.float64)[:, None] * scol.astype(np.float64)[None, :] / 16129.0
+    assert np.all(np.abs(y64 - ref) <= 1e-14 * np.abs(ref))
+    assert np.all(np.abs(y32.astype(np.float64) - ref) <= 3.0 * 2.0 ** -24 * np.abs(ref) * (1 + 2.0 ** -20))
+    # a column with state 0 (an all-zero weight row) gives a zero output column
+    scol[7] = 0.0
+    assert not oracle.dequantize_rowcol(acc, srow, scol)[:, 7].any()
+
+
+def test_colwise_transpose_quantizer(oracle):
+    """Every column gets its own scale: the absmax element of each column maps to +-127, the error bound holds per
+    column, and the result equals quantizing column by column with the (pinned) row-wise quantizer."""
+    rng = np.random.default_rng(42)
+    w = rand_bf16(rng, (48, 32), 0.2)
+    w[:, 5] = bf(f32(w[:, 5]) * 64.0)                       # one column on a very different scale
+    q_t, s = oracle.quantize_colwise_transpose(w)
+    assert q_t.shape == (32, 48) and s.shape == (32,)
+    wv = f32(w).astype(np.float64)
+    np.testing.assert_array_equal(s, np.abs(f32(w)).max(axis=0))
+    assert np.all(np.abs(q_t).max(axis=1) == 127)
+    err = np.abs(wv.T - s.astype(np.float64)[:, None] * q_t / 127.0)
+    assert np.all(err <= s.astype(np.float64)[:, None] / 254.0 * (1 + 2.0 ** -14))
+    for k in (0, 5, 31):
+        qk, sk = oracle.quantize_rowwise(np.ascontiguousarray(w[:, k:k + 1].T))
+        np.testing.assert_array_equal(q_t[k], qk[0])
+        assert s[k] == sk[0]
+
+
+def test_switchback_q_layer_bounds(oracle):
+    """Forward and input gradient of SwitchBackQ against the binary64 products of the bf16 inputs: deterministic bound
+    with per-row (forward) and per-column (backward) weight steps; finer weight scales may not be worse than the
+    tensor-wise ones on a weight whose rows differ in scale."""
+    d = I.make_layer_inputs("tiny")
+    x, w, dy = d["x"][:96, :128], d["w"][:64, :128].copy(), d["dy"][:96, :64]
+    scale_rows = np.exp2(np.arange(64) % 5).astype(np.float32)
+    w = bf(f32(w) * scale_rows[:, None])                    # heterogeneous output features
+    xv, wv, gv = f32(x).astype(np.float64), f32(w).astype(np.float64), f32(dy).astype(np.float64)
+    f = oracle.forward_q(x, w)
+    dx_, dw_ = f["state_x"].astype(np.float64) / 254 * (1 + 2.0 ** -14), f["state_w"].astype(np.float64) / 254 * (1 + 2.0 ** -14)
+    bound = np.abs(xv) @ np.ones_like(wv).T * dw_[None, :] + dx_[:, None] * (np.ones_like(xv) @ np.abs(wv).T) \
+        + 128 * dx_[:, None] * dw_[None, :]
+    ref = xv @ wv.T
+    assert np.all(np.abs(f["y32"] - ref) <= bound + 1e-5 * np.abs(ref) + 1e-30)
+    ft = oracle.forward(x, w)
+    assert np.sqrt(((f["y32"] - ref) ** 2).mean()) < np.sqrt(((ft["y32"] - ref) ** 2).mean())
+    g = oracle.backward_input_q(dy, w)
+    dg_, dc_ = g["state_g"].astype(np.float64) / 254 * (1 + 2.0 ** -14), g["state_wc"].astype(np.float64) / 254 * (1 + 2.0 ** -14)
+    refx = gv @ wv
+    boundx = np.abs(gv) @ np.ones_like(wv) * dc_[None, :] + dg_[:, None] * (np.ones_like(gv) @ np.abs(wv)) \
+        + 64 * dg_[:, None] * dc_[None, :]
+    assert np.all(np.abs(g["dx32"] - refx) <= boundx + 1e-5 * np.abs(refx) + 1e-30)
+    np.testing.assert_array_equal(g["dx_bf16"], oracle.round_to_bf16(g["dx32"]))
