@@ -111,6 +111,18 @@ def main():
             sb.backward_input(t["dy"], t["bufs"], dx=t["dx"])
             sb.backward_weight_m(t["dy"], t["bufs"], x_hat=x_hat[: L.b * L.n].view(L.b, L.n), dw=t["dw"])
 
+    q_bufs = {}
+
+    def switchback_q_step():
+        # SwitchBackQ: row-wise weight quantization in the forward pass, column-wise (transposed) in the backward pass.
+        for i, t in enumerate(layers):
+            L = t["L"]
+            if i not in q_bufs:
+                q_bufs[i] = sb.LayerBuffersQ(L.b, L.n, L.m, dev)
+            sb.forward_q(t["x"], t["w"], bufs=q_bufs[i], y=t["y"])
+            sb.backward_input_q(t["dy"], t["w"], q_bufs[i], dx=t["dx"])
+            sb.backward_weight(t["dy"], t["x"], t["bufs"], dw=t["dw"])
+
     def bf16_step():
         for t in layers:
             torch.matmul(t["x"], t["w"].t(), out=t["y"])
@@ -135,6 +147,8 @@ def main():
     bf_ms, _ = timed(bf16_step, args.steps, args.warmup)
     requant_ms, _ = timed(switchback_step_requant, max(3, args.steps // 2), 2)
     variant_m_ms, _ = timed(switchback_m_step, max(3, args.steps // 2), 2)
+    variant_q_ms, _ = timed(switchback_q_step, max(3, args.steps // 2), 2)
+    q_bufs.clear()
 
     # ---- per-kernel times: the same kernels on the same shapes, one event pair around each launch group ------
     ops = {}  # name -> [total ms over reps, algorithmic work, unit kind]
@@ -243,6 +257,7 @@ def main():
         "wall_ms_per_step": round(sb_wall_ms, 4),
         "ms_per_step_w_requantized_in_backward": round(requant_ms, 4),
         "ms_per_step_switchback_m": round(variant_m_ms, 4),
+        "ms_per_step_switchback_q": round(variant_q_ms, 4),
         "roofline": roofline,
         "kernels": kernels,
         "sum_of_kernel_ms": round(op_sum, 4),

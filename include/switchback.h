@@ -49,7 +49,8 @@ typedef enum {
     SB_OP_QUANTIZE_TENSORWISE = 0,
     SB_OP_FORWARD = 1,
     SB_OP_BACKWARD_INPUT = 2,
-    SB_OP_BACKWARD_WEIGHT = 3
+    SB_OP_BACKWARD_WEIGHT = 3,
+    SB_OP_QUANTIZE_COLWISE = 4 /* also the workspace of switchback_backward_input_q; pass rows as m, cols as n */
 } sb_op;
 
 /* What the forward pass leaves for the backward pass (Algorithm 1 saves X and W in 16 bit and re-quantizes W in
@@ -126,6 +127,30 @@ int switchback_dequantize_rowwise(const int8_t *q, const float *state, int64_t r
 int switchback_backward_weight_m(const void *dy_bf16, const sb_saved *saved, int64_t b, int64_t n, int64_t m,
                                  void *x_hat_bf16, void *dw, sb_dtype dw_dtype, void *ws, size_t ws_bytes,
                                  void *stream);
+
+/* The variant SwitchBackQ (the appendix algorithm with row-wise and column-wise quantization of the weights; its
+ * forward pass is 1/127^2 * state_row(X) state_row(W)^T * (Q_row(X) Q_row(W)^T), the equation that follows the
+ * variants paragraph of Section 2.2.1).  Both operands of a product then carry one state per row of their code
+ * matrix, evaluated as c_j = state_b[j]/16129, fl(state_a[i] * c_j), fl((float)acc * that), bf16 by RNE.
+ *
+ * switchback_quantize_colwise_transpose ("column-wise_quantize_transpose"): one absmax per COLUMN of w [rows,cols];
+ *   q_t [cols,rows] int8 (transposed codes), state [cols] f32.  Equal to switchback_quantize_rowwise of the
+ *   transposed matrix.  rows % 16 == 0, cols % 16 == 0; ws: SB_OP_QUANTIZE_COLWISE workspace.
+ * switchback_matmul_int8_dequant_rc: out[i,j] = state_a[i] * state_b[j] / 127^2 * sum_k aq[i,k] bq[j,k];
+ *   aq [M,K], state_a [M], bq [N,K], state_b [N]; out [M,N] SB_BF16 or SB_F32; shape limits as the tensor-wise call.
+ * switchback_forward_q: Y = dequant(Q_row(X) Q_row(W)^T); fills xq [b,n], state_x [b], wq [m,n], state_w_row [m].
+ * switchback_backward_input_q: dX = dequant(Q_row(dY) Q_col(W)); fills gq [b,m], state_g [b], wq_t [n,m],
+ *   state_w_col [n] (W is quantized again from its 16-bit values, as the algorithm does); ws as above.
+ * The weight gradient of the variant is switchback_backward_weight. */
+int switchback_quantize_colwise_transpose(const void *w_bf16, int64_t rows, int64_t cols, int8_t *q_t, float *state,
+                                          void *ws, size_t ws_bytes, void *stream);
+int switchback_matmul_int8_dequant_rc(const int8_t *aq, const float *state_a, const int8_t *bq, const float *state_b,
+                                      int64_t M, int64_t N, int64_t K, void *out, sb_dtype out_dtype, void *stream);
+int switchback_forward_q(const void *x_bf16, const void *w_bf16, int64_t b, int64_t n, int64_t m, void *y,
+                         sb_dtype y_dtype, int8_t *xq, float *state_x, int8_t *wq, float *state_w_row, void *stream);
+int switchback_backward_input_q(const void *dy_bf16, const void *w_bf16, int64_t b, int64_t n, int64_t m, void *dx,
+                                sb_dtype dx_dtype, int8_t *gq, float *state_g, int8_t *wq_t, float *state_w_col,
+                                void *ws, size_t ws_bytes, void *stream);
 
 /* Bytes of device workspace `op` needs for a layer of this shape (0 if none).  Shape arguments an op does not
  * use are ignored (for SB_OP_QUANTIZE_TENSORWISE pass rows as m and cols as n). */

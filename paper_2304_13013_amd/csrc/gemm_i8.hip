@@ -9,6 +9,8 @@ namespace {
 // 64-byte k-steps with four stages, every wave loading.
 typedef GemmI8Cfg<128, 2, 4, 3, 1> K128;
 typedef GemmI8Cfg<64, 4, 8, 4, 1> K64;
+// Row-and-column scales (SwitchBackQ): the 32 column states a lane keeps need the registers of the even split.
+typedef GemmI8Cfg<128, 2, 4, 4, 1> K128Q;
 
 #define SB_GEMM_I8_ENTRY(name, CFG, OUT) \
     __global__ __launch_bounds__(CFG::THREADS) void name(GemmI8Args p) { gemm_i8_dequant_body<CFG, OUT>(p); }
@@ -18,6 +20,13 @@ SB_GEMM_I8_ENTRY(gemm_i8_k128_i32, K128, OUT_I32)
 SB_GEMM_I8_ENTRY(gemm_i8_k64_bf16, K64, OUT_BF16)
 SB_GEMM_I8_ENTRY(gemm_i8_k64_f32, K64, OUT_F32)
 SB_GEMM_I8_ENTRY(gemm_i8_k64_i32, K64, OUT_I32)
+#define SB_GEMM_I8_ENTRY_Q(name, CFG, OUT) \
+    __global__ __launch_bounds__(CFG::THREADS) void name(GemmI8Args p) { gemm_i8_dequant_body<CFG, OUT, true>(p); }
+SB_GEMM_I8_ENTRY_Q(gemm_i8q_k128_bf16, K128Q, OUT_BF16)
+SB_GEMM_I8_ENTRY_Q(gemm_i8q_k128_f32, K128Q, OUT_F32)
+SB_GEMM_I8_ENTRY_Q(gemm_i8q_k64_bf16, K64, OUT_BF16)
+SB_GEMM_I8_ENTRY_Q(gemm_i8q_k64_f32, K64, OUT_F32)
+#undef SB_GEMM_I8_ENTRY_Q
 #undef SB_GEMM_I8_ENTRY
 
 int cached_num_cu() {
@@ -49,10 +58,18 @@ hipError_t launch(void (*kernel)(GemmI8Args), bool *attr_set, GemmI8Args args, h
 }  // namespace
 
 hipError_t launch_gemm_i8_dequant(const int8_t *aq, const float *state_row, const int8_t *bq,
-                                  const float *state_tensor, int64_t M, int64_t N, int64_t K, void *out,
-                                  sb_dtype out_dtype, hipStream_t stream) {
+                                  const float *state_tensor, const float *state_col, int64_t M, int64_t N,
+                                  int64_t K, void *out, sb_dtype out_dtype, hipStream_t stream) {
     if (M == 0 || N == 0) return hipSuccess;
-    GemmI8Args args{aq, bq, state_row, state_tensor, out, (int)M, (int)N, (int)K, 0, 0, 8};
+    GemmI8Args args{aq, bq, state_row, state_tensor, state_col, out, (int)M, (int)N, (int)K, 0, 0, 8};
+    if (state_col != nullptr && out_dtype != SB_I32_RAW) {
+        static bool q_attr_set[4] = {false, false, false, false};
+        if (K % 128 == 0)
+            return out_dtype == SB_BF16 ? launch<K128Q>(gemm_i8q_k128_bf16, &q_attr_set[0], args, stream)
+                                        : launch<K128Q>(gemm_i8q_k128_f32, &q_attr_set[1], args, stream);
+        return out_dtype == SB_BF16 ? launch<K64>(gemm_i8q_k64_bf16, &q_attr_set[2], args, stream)
+                                    : launch<K64>(gemm_i8q_k64_f32, &q_attr_set[3], args, stream);
+    }
     static bool attr_set[6] = {false, false, false, false, false, false};
     const bool wide = K % 128 == 0;
     switch (out_dtype) {

@@ -81,7 +81,8 @@ struct GemmI8Args {
     const int8_t *a;
     const int8_t *b;
     const float *state_row;
-    const float *state_tensor;
+    const float *state_tensor;  // [1]; unused by the row-and-column variant
+    const float *state_col;     // [N], row-and-column variant only (SwitchBackQ: one weight state per output column)
     void *out;
     int M, N, K;  // M*K and N*K must stay below 2^32 (32-bit buffer offsets)
     int tiles_m, tiles_n;
@@ -152,12 +153,13 @@ __device__ __forceinline__ void wait_stage(int later) {
 
 // What one wave does: an (MT*32) x 64 part of the workgroup's tile, rows from wm0.  Every role runs the same
 // sequence of barriers.
-template <class C, int OUT, int MT>
+// COLSCALE: out[i,j] = (float)acc * fl(state_row[i] * fl(state_col[j] / 127^2)) instead of the tensor-wise scale.
+template <class C, int OUT, int MT, bool COLSCALE>
 __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const int wave, const int wm0) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     typedef __attribute__((address_space(3))) void lds_void;
     constexpr int S = C::STAGES;
-    constexpr int NSCALE = OUT != OUT_I32 ? MT : 0;  // per-lane row-scale loads per tile
+    constexpr int NSCALE = OUT != OUT_I32 ? MT + (COLSCALE ? C::NT * 4 : 0) : 0;  // per-lane scale loads per tile
     constexpr int NFRAG = MT + C::NT;
     constexpr int EPI_STORES = MT * C::STORES_PER_BLOCK;  // 16-byte global stores per lane per tile
 
@@ -254,7 +256,7 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
 
     // c = state_tensor / 127^2, read once (the pointer may alias nothing the kernel writes).
     float tensor_scale = 0.0f;
-    if (OUT != OUT_I32) tensor_scale = p.state_tensor[0] / 16129.0f;
+    if (OUT != OUT_I32 && !COLSCALE) tensor_scale = p.state_tensor[0] / 16129.0f;
     asm volatile("" : "+v"(tensor_scale));
 
     // ---- Work list.  A segment is the k-tile range [kb, ke) of one output tile; segment i of this workgroup is the
@@ -358,11 +360,22 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
         // Row absmax values of this tile, requested now so that the epilogue finds them in registers.  Inline asm with
         // a counted wait: the compiler's own wait would drain the stages in flight.
         float srow[MT];
+        v4f scol[COLSCALE ? C::NT : 1][4];
         if (OUT != OUT_I32) {
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
                 const float *src = p.state_row + min(tm * C::BM + wm0 + mt * 32 + frow, p.M - 1);
                 asm volatile("global_load_dword %0, %1, off" : "=v"(srow[mt]) : "v"(src) : "memory");
+            }
+            if (COLSCALE) {
+                // The column states of this lane's accumulator quads: columns nt*32 + 8q + 4*(lane/32) .. +3.
+#pragma unroll
+                for (int nt = 0; nt < C::NT; ++nt)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const float *src = p.state_col + min(tn * C::BN + wn0 + nt * 32 + 8 * q + 4 * fhalf, p.N - 4);
+                        asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(scol[nt][q]) : "v"(src) : "memory");
+                    }
             }
             note_vmem(NSCALE);
             younger_scale = 0;
@@ -463,7 +476,16 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) asm volatile("" : "+v"(srow[mt]));
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) rscale[mt] = srow[mt] * tensor_scale;
+            for (int mt = 0; mt < MT; ++mt) rscale[mt] = COLSCALE ? srow[mt] : srow[mt] * tensor_scale;
+            if (COLSCALE) {
+#pragma unroll
+                for (int nt = 0; nt < C::NT; ++nt)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        asm volatile("" : "+v"(scol[nt][q]));
+                        scol[nt][q] = scol[nt][q] / 16129.0f;  // c_j = state_col[j] / 127^2, correctly rounded
+                    }
+            }
         }
 
         // The epilogue needs no barrier: the patch is private to the wave, and the next segment's first stages are
@@ -486,7 +508,8 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
                         v4f v;
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
-                            v[e] = (float)(acc[mt][nt][4 * q + e]) * rscale[mt];
+                            v[e] = (float)(acc[mt][nt][4 * q + e]) *
+                                   (COLSCALE ? rscale[mt] * scol[nt][q][e] : rscale[mt]);
                         const int piece = (nt * 4 + q) ^ (frow & 7);
                         *reinterpret_cast<v4bf *>(epi + frow * (C::WTN * 2) + piece * 16 + fhalf * 8) =
                             __builtin_convertvector(v, v4bf);
@@ -523,7 +546,8 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
                                 v4f v;
 #pragma unroll
                                 for (int e = 0; e < 4; ++e)
-                                    v[e] = (float)(acc[mt][nt][4 * q + e]) * rscale[mt];
+                                    v[e] = (float)(acc[mt][nt][4 * q + e]) *
+                                   (COLSCALE ? rscale[mt] * scol[nt][q][e] : rscale[mt]);
                                 *reinterpret_cast<v4f *>(static_cast<float *>(p.out) + (int64_t)gr * p.N + gc) = v;
                             } else {
                                 v4i v;
@@ -548,15 +572,15 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
 
 // The kernel body.  It is a __device__ template called from non-template __global__ entry points: a __global__
 // template that uses device-only buffer builtins does not instantiate in the host pass.
-template <class C, int OUT>
+template <class C, int OUT, bool COLSCALE = false>
 __device__ __forceinline__ void gemm_i8_dequant_body(const GemmI8Args &p) {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform: what derives from it is scalar
     if (C::MT_LOADER == 4)
-        gemm_i8_dequant_role<C, OUT, 4>(p, wave, (wave / C::WAVES_N) * C::WTM);
+        gemm_i8_dequant_role<C, OUT, 4, COLSCALE>(p, wave, (wave / C::WAVES_N) * C::WTM);
     else if (wave < C::LOADERS)
-        gemm_i8_dequant_role<C, OUT, C::MT_LOADER>(p, wave, 0);
+        gemm_i8_dequant_role<C, OUT, C::MT_LOADER, COLSCALE>(p, wave, 0);
     else
-        gemm_i8_dequant_role<C, OUT, 8 - C::MT_LOADER>(p, wave, C::MT_LOADER * 32);
+        gemm_i8_dequant_role<C, OUT, 8 - C::MT_LOADER, COLSCALE>(p, wave, C::MT_LOADER * 32);
 }
 
 // Launch geometry shared by the entry points: persistent grid, a multiple of the XCD count.

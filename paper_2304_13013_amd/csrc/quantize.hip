@@ -233,6 +233,80 @@ __global__ __launch_bounds__(256) void quantize_tensorwise_kernel(const v4u *__r
     }
 }
 
+// ---- column-wise quantization fused with a transpose (SwitchBackQ backward) -----------------------------------
+// Every column of w [rows, cols] has its own absmax; the codes leave transposed, q_t [cols, rows], with
+// state [cols].  Pass 1: the rows are cut into gridDim.y runs, and each block keeps, per 8-column chunk, packed
+// 16-bit maxima over its run (no atomics, deterministic).  Pass 2: a 128x128 tile; its 128 column scales are
+// finished from the partial maxima first, then the tile is quantized element by element with its column's scale
+// and written out through the same LDS transpose as the tensor-wise kernel.
+__global__ __launch_bounds__(256) void col_absmax_partial_kernel(const v4u *__restrict__ w, int rows, int chunks,
+                                                                 v4u *__restrict__ partials) {
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= chunks) return;
+    const int per = (rows + gridDim.y - 1) / gridDim.y;
+    const int r0 = blockIdx.y * per, r1 = min(rows, r0 + per);
+    v4u m = {0u, 0u, 0u, 0u};
+    for (int r = r0; r < r1; ++r) {
+        const v4u v = w[(int64_t)r * chunks + c];
+        m.x = pk_absmax_u16(m.x, v.x);
+        m.y = pk_absmax_u16(m.y, v.y);
+        m.z = pk_absmax_u16(m.z, v.z);
+        m.w = pk_absmax_u16(m.w, v.w);
+    }
+    partials[(int64_t)blockIdx.y * chunks + c] = m;
+}
+
+__global__ __launch_bounds__(256) void quantize_colwise_transpose_kernel(const v4u *__restrict__ w, int rows, int cols,
+                                                                         int8_t *__restrict__ q_t,
+                                                                         float *__restrict__ state,
+                                                                         const unsigned short *__restrict__ partials,
+                                                                         int nparts) {
+    __shared__ float tcol[kTile];
+    __shared__ __attribute__((aligned(16))) unsigned char tile_t[kTile * kTileStride];
+    const int r0 = blockIdx.y * kTile, c0 = blockIdx.x * kTile;
+    if (threadIdx.x < kTile) {
+        const int c = c0 + threadIdx.x;
+        float t = 0.0f;
+        if (c < cols) {
+            unsigned int m = 0;  // partials: [run][column] 16-bit patterns (the packed chunks, read back per column)
+            for (int i = 0; i < nparts; ++i) m = max(m, (unsigned int)partials[(int64_t)i * cols + c]);
+            float s;
+            t = scale_from_absmax_bits(m, &s);
+            if (blockIdx.y == 0) state[c] = s;
+        }
+        tcol[threadIdx.x] = t;
+    }
+    __syncthreads();
+    const int chunks_per_row = cols >> 3;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int id = threadIdx.x + 256 * i;
+        const int lr = id >> 4, lc = (id & 15) << 3;  // local row, local first column of the 8-element chunk
+        const int r = r0 + lr, c = c0 + lc;
+        if (r < rows && c < cols) {
+            const v4u v = w[(int64_t)r * chunks_per_row + (c >> 3)];
+            const unsigned int d[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                tile_t[(lc + 2 * j) * kTileStride + lr] =
+                    (unsigned char)code_bits(__uint_as_float(d[j] << 16), tcol[lc + 2 * j]);
+                tile_t[(lc + 2 * j + 1) * kTileStride + lr] =
+                    (unsigned char)code_bits(__uint_as_float(d[j] & 0xffff0000u), tcol[lc + 2 * j + 1]);
+            }
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int id = threadIdx.x + 256 * i;
+        const int lc = id >> 3, lr = (id & 7) << 4;  // one 16-byte piece of a transposed row
+        const int c = c0 + lc, r = r0 + lr;
+        if (c < cols && r < rows)
+            *reinterpret_cast<v4u *>(q_t + (int64_t)c * rows + r) =
+                *reinterpret_cast<const v4u *>(tile_t + lc * kTileStride + lr);
+    }
+}
+
 // Row-wise dequantization of the memory-efficient variant (SwitchBackM, the appendix algorithm that saves only the
 // int8 codes of X): x^[i,j] = bf16(fl((float)q[i,j] * fl(state[i] / 127))), the row-wise quantization equation read
 // backwards.  One wavefront per row, 8 codes (8 bytes in, 16 bytes out) per lane and step.
@@ -265,6 +339,29 @@ hipError_t launch_dequantize_rowwise(const int8_t *q, const float *state, int64_
     if (rows == 0) return hipSuccess;
     dequantize_rowwise_kernel<<<(unsigned int)((rows + 3) / 4), 256, 0, stream>>>(
         reinterpret_cast<const v2u *>(q), state, rows, (int)(cols / 8), static_cast<v4u *>(x_hat));
+    return hipGetLastError();
+}
+
+int colwise_row_runs(int64_t rows) {
+    const int64_t r = (rows + 15) / 16;
+    return (int)(r < 1 ? 1 : (r > kColwiseRuns ? kColwiseRuns : r));
+}
+
+size_t quantize_colwise_workspace_bytes(int64_t rows, int64_t cols) {
+    return (size_t)colwise_row_runs(rows) * (size_t)cols * sizeof(unsigned short);
+}
+
+hipError_t launch_quantize_colwise_transpose(const void *w, int64_t rows, int64_t cols, int8_t *q_t, float *state,
+                                             void *partials, hipStream_t stream) {
+    const int chunks = (int)(cols / 8), runs = colwise_row_runs(rows);
+    const v4u *wp = static_cast<const v4u *>(w);
+    col_absmax_partial_kernel<<<dim3((unsigned int)((chunks + 255) / 256), (unsigned int)runs), 256, 0, stream>>>(
+        wp, (int)rows, chunks, static_cast<v4u *>(partials));
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    dim3 grid((unsigned int)((cols + kTile - 1) / kTile), (unsigned int)((rows + kTile - 1) / kTile));
+    quantize_colwise_transpose_kernel<<<grid, 256, 0, stream>>>(wp, (int)rows, (int)cols, q_t, state,
+                                                                static_cast<const unsigned short *>(partials), runs);
     return hipGetLastError();
 }
 

@@ -33,15 +33,20 @@ hipError_t launch_quantize_rowwise(const void *x, int64_t rows, int64_t cols, in
                                    hipStream_t stream);
 hipError_t launch_dequantize_rowwise(const int8_t *q, const float *state, int64_t rows, int64_t cols, void *x_hat,
                                      hipStream_t stream);
+size_t quantize_colwise_workspace_bytes(int64_t rows, int64_t cols);
+hipError_t launch_quantize_colwise_transpose(const void *w, int64_t rows, int64_t cols, int8_t *q_t, float *state,
+                                             void *partials, hipStream_t stream);
 hipError_t launch_quantize_tensorwise(const void *w, int64_t rows, int64_t cols, int8_t *q, int8_t *q_t,
                                       float *state, unsigned int *partials, hipStream_t stream);
+// state_col == nullptr: tensor-wise weight state (state_tensor[0]); else one state per output column (SwitchBackQ).
 hipError_t launch_gemm_i8_dequant(const int8_t *aq, const float *state_row, const int8_t *bq,
-                                  const float *state_tensor, int64_t M, int64_t N, int64_t K, void *out,
-                                  sb_dtype out_dtype, hipStream_t stream);
+                                  const float *state_tensor, const float *state_col, int64_t M, int64_t N,
+                                  int64_t K, void *out, sb_dtype out_dtype, hipStream_t stream);
 size_t gemm_bf16_tn_workspace_bytes(int64_t b, int64_t n, int64_t m);
 hipError_t launch_gemm_bf16_tn(const void *dy, const void *x, int64_t b, int64_t n, int64_t m, void *dw,
                                sb_dtype dw_dtype, void *ws, hipStream_t stream);
 
 constexpr int kTensorwisePartials = 1024;  // upper bound on blocks of the tensor-wise absmax pass
+constexpr int kColwiseRuns = 64;  // upper bound on the row runs of the column-wise absmax pass
 
 }  // namespace sb

@@ -68,7 +68,7 @@ int switchback_matmul_int8_dequant(const int8_t *aq, const float *state_row, con
     if (M == 0) return SB_OK;
     if (!ok_ptr(aq) || !ok_ptr(bq) || !ok_ptr(out)) return SB_INVALID_ARG;
     if (out_dtype != SB_I32_RAW && (state_row == nullptr || state_tensor == nullptr)) return SB_INVALID_ARG;
-    return from_hip(sb::launch_gemm_i8_dequant(aq, state_row, bq, state_tensor, M, N, K, out, out_dtype,
+    return from_hip(sb::launch_gemm_i8_dequant(aq, state_row, bq, state_tensor, nullptr, M, N, K, out, out_dtype,
                                                static_cast<hipStream_t>(stream)));
 }
 
@@ -92,7 +92,7 @@ int switchback_forward(const void *x_bf16, const void *w_bf16, int64_t b, int64_
     if (b == 0) return SB_OK;
     e = sb::launch_quantize_rowwise(x_bf16, b, n, saved->xq, saved->state_x, s);
     if (e != hipSuccess) return SB_HIP_ERROR;
-    return from_hip(sb::launch_gemm_i8_dequant(saved->xq, saved->state_x, saved->wq, saved->state_w, b, m, n, y,
+    return from_hip(sb::launch_gemm_i8_dequant(saved->xq, saved->state_x, saved->wq, saved->state_w, nullptr, b, m, n, y,
                                                y_dtype, s));
 }
 
@@ -110,7 +110,7 @@ int switchback_backward_input(const void *dy_bf16, const sb_saved *saved, int64_
     // was kept by the forward pass; dX = int8 matmul over m fused with the dequantization.
     hipError_t e = sb::launch_quantize_rowwise(dy_bf16, b, m, gq, state_g, s);
     if (e != hipSuccess) return SB_HIP_ERROR;
-    return from_hip(sb::launch_gemm_i8_dequant(gq, state_g, saved->wq_t, saved->state_w, b, n, m, dx, dx_dtype, s));
+    return from_hip(sb::launch_gemm_i8_dequant(gq, state_g, saved->wq_t, saved->state_w, nullptr, b, n, m, dx, dx_dtype, s));
 }
 
 int switchback_backward_weight(const void *dy_bf16, const void *x_bf16, int64_t b, int64_t n, int64_t m,
@@ -149,6 +149,68 @@ int switchback_backward_weight_m(const void *dy_bf16, const sb_saved *saved, int
     return switchback_backward_weight(dy_bf16, x_hat_bf16, b, n, m, dw, dw_dtype, ws, ws_bytes, stream);
 }
 
+int switchback_quantize_colwise_transpose(const void *w_bf16, int64_t rows, int64_t cols, int8_t *q_t, float *state,
+                                          void *ws, size_t ws_bytes, void *stream) {
+    if (rows <= 0 || cols <= 0) return SB_INVALID_ARG;
+    if (rows % 16 || cols % 16 || rows > (int64_t)1 << 24 || cols > (int64_t)1 << 24) return SB_UNSUPPORTED_SHAPE;
+    if (!ok_ptr(w_bf16) || !ok_ptr(q_t) || state == nullptr) return SB_INVALID_ARG;
+    if (ws == nullptr || !aligned16(ws)) return SB_INVALID_ARG;
+    if (ws_bytes < sb::quantize_colwise_workspace_bytes(rows, cols)) return SB_WORKSPACE_TOO_SMALL;
+    return from_hip(sb::launch_quantize_colwise_transpose(w_bf16, rows, cols, q_t, state, ws,
+                                                          static_cast<hipStream_t>(stream)));
+}
+
+int switchback_matmul_int8_dequant_rc(const int8_t *aq, const float *state_a, const int8_t *bq, const float *state_b,
+                                      int64_t M, int64_t N, int64_t K, void *out, sb_dtype out_dtype, void *stream) {
+    if (M < 0 || N <= 0 || K <= 0 || (out_dtype != SB_BF16 && out_dtype != SB_F32)) return SB_INVALID_ARG;
+    if (K % 64 || N % 64 || K > kMaxIntK || N > kMaxIntK || M > (int64_t)1 << 30) return SB_UNSUPPORTED_SHAPE;
+    if ((M + 256) * K >= (int64_t)1 << 32 || (N + 256) * K >= (int64_t)1 << 32) return SB_UNSUPPORTED_SHAPE;
+    if (M * N * 2 >= (int64_t)1 << 32) return SB_UNSUPPORTED_SHAPE;
+    if (M == 0) return SB_OK;
+    if (!ok_ptr(aq) || !ok_ptr(bq) || !ok_ptr(out) || state_a == nullptr || !ok_ptr(state_b)) return SB_INVALID_ARG;
+    return from_hip(sb::launch_gemm_i8_dequant(aq, state_a, bq, nullptr, state_b, M, N, K, out, out_dtype,
+                                               static_cast<hipStream_t>(stream)));
+}
+
+int switchback_forward_q(const void *x_bf16, const void *w_bf16, int64_t b, int64_t n, int64_t m, void *y,
+                         sb_dtype y_dtype, int8_t *xq, float *state_x, int8_t *wq, float *state_w_row, void *stream) {
+    int st = layer_shape_status(b, n, m);
+    if (st != SB_OK) return st;
+    if (y_dtype != SB_BF16 && y_dtype != SB_F32) return SB_INVALID_ARG;
+    if (!ok_ptr(w_bf16) || !ok_ptr(wq) || !ok_ptr(state_w_row)) return SB_INVALID_ARG;
+    if (b > 0 && (!ok_ptr(x_bf16) || !ok_ptr(y) || !ok_ptr(xq) || state_x == nullptr)) return SB_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // SwitchBackQ forward: X_int8, state_X = row-wise quantize(X); W_int8, state_W = row-wise quantize(W); int8
+    // matmul fused with the row-and-column dequantization.
+    hipError_t e = sb::launch_quantize_rowwise(w_bf16, m, n, wq, state_w_row, s);
+    if (e != hipSuccess) return SB_HIP_ERROR;
+    if (b == 0) return SB_OK;
+    e = sb::launch_quantize_rowwise(x_bf16, b, n, xq, state_x, s);
+    if (e != hipSuccess) return SB_HIP_ERROR;
+    return from_hip(sb::launch_gemm_i8_dequant(xq, state_x, wq, nullptr, state_w_row, b, m, n, y, y_dtype, s));
+}
+
+int switchback_backward_input_q(const void *dy_bf16, const void *w_bf16, int64_t b, int64_t n, int64_t m, void *dx,
+                                sb_dtype dx_dtype, int8_t *gq, float *state_g, int8_t *wq_t, float *state_w_col,
+                                void *ws, size_t ws_bytes, void *stream) {
+    int st = layer_shape_status(b, n, m);
+    if (st != SB_OK) return st;
+    if (dx_dtype != SB_BF16 && dx_dtype != SB_F32) return SB_INVALID_ARG;
+    if (!ok_ptr(w_bf16) || !ok_ptr(wq_t) || !ok_ptr(state_w_col)) return SB_INVALID_ARG;
+    if (b > 0 && (!ok_ptr(dy_bf16) || !ok_ptr(dx) || !ok_ptr(gq) || state_g == nullptr)) return SB_INVALID_ARG;
+    if (ws == nullptr || !aligned16(ws)) return SB_INVALID_ARG;
+    if (ws_bytes < sb::quantize_colwise_workspace_bytes(m, n)) return SB_WORKSPACE_TOO_SMALL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // SwitchBackQ backward: G_int8 = row-wise quantize(dY); W_int8, state_W = column-wise quantize transpose(W); the
+    // contraction runs over m, with one state per token and one per input feature.
+    hipError_t e = sb::launch_quantize_colwise_transpose(w_bf16, m, n, wq_t, state_w_col, ws, s);
+    if (e != hipSuccess) return SB_HIP_ERROR;
+    if (b == 0) return SB_OK;
+    e = sb::launch_quantize_rowwise(dy_bf16, b, m, gq, state_g, s);
+    if (e != hipSuccess) return SB_HIP_ERROR;
+    return from_hip(sb::launch_gemm_i8_dequant(gq, state_g, wq_t, nullptr, state_w_col, b, n, m, dx, dx_dtype, s));
+}
+
 size_t switchback_workspace_bytes(int op, int64_t b, int64_t n, int64_t m) {
     switch (op) {
         case SB_OP_QUANTIZE_TENSORWISE:
@@ -157,6 +219,9 @@ size_t switchback_workspace_bytes(int op, int64_t b, int64_t n, int64_t m) {
         case SB_OP_BACKWARD_WEIGHT:
             if (b < 0 || n <= 0 || m <= 0) return 0;
             return sb::gemm_bf16_tn_workspace_bytes(b, n, m);
+        case SB_OP_QUANTIZE_COLWISE:  // w is [m, n]
+            if (n <= 0 || m <= 0) return 0;
+            return sb::quantize_colwise_workspace_bytes(m, n);
         default: return 0;
     }
 }

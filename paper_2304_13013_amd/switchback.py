@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libswitchback.so")
 
 SB_BF16, SB_F32, SB_I32_RAW = 0, 1, 2
-SB_OP_QUANTIZE_TENSORWISE, SB_OP_FORWARD, SB_OP_BACKWARD_INPUT, SB_OP_BACKWARD_WEIGHT = 0, 1, 2, 3
+SB_OP_QUANTIZE_TENSORWISE, SB_OP_FORWARD, SB_OP_BACKWARD_INPUT, SB_OP_BACKWARD_WEIGHT, SB_OP_QUANTIZE_COLWISE = 0, 1, 2, 3, 4
 
 _TORCH_DTYPE = {SB_BF16: torch.bfloat16, SB_F32: torch.float32, SB_I32_RAW: torch.int32}
 _SB_DTYPE = {v: k for k, v in _TORCH_DTYPE.items()}
@@ -51,13 +51,19 @@ def load_library():
     lib.switchback_backward_weight.argtypes = [vp, vp, i64, i64, i64, vp, ci, vp, sz, vp]
     lib.switchback_dequantize_rowwise.argtypes = [vp, vp, i64, i64, vp, vp]
     lib.switchback_backward_weight_m.argtypes = [vp, ctypes.POINTER(SbSaved), i64, i64, i64, vp, vp, ci, vp, sz, vp]
+    lib.switchback_quantize_colwise_transpose.argtypes = [vp, i64, i64, vp, vp, vp, sz, vp]
+    lib.switchback_matmul_int8_dequant_rc.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, ci, vp]
+    lib.switchback_forward_q.argtypes = [vp, vp, i64, i64, i64, vp, ci, vp, vp, vp, vp, vp]
+    lib.switchback_backward_input_q.argtypes = [vp, vp, i64, i64, i64, vp, ci, vp, vp, vp, vp, vp, sz, vp]
     lib.switchback_workspace_bytes.argtypes = [ci, i64, i64, i64]
     lib.switchback_workspace_bytes.restype = sz
     lib.switchback_status_string.argtypes = [ci]
     lib.switchback_status_string.restype = ctypes.c_char_p
     for name in ("switchback_quantize_rowwise", "switchback_quantize_tensorwise", "switchback_matmul_int8_dequant",
                  "switchback_forward", "switchback_backward_input", "switchback_backward_weight",
-                 "switchback_dequantize_rowwise", "switchback_backward_weight_m"):
+                 "switchback_dequantize_rowwise", "switchback_backward_weight_m",
+                 "switchback_quantize_colwise_transpose", "switchback_matmul_int8_dequant_rc",
+                 "switchback_forward_q", "switchback_backward_input_q"):
         getattr(lib, name).restype = ci
     _lib = lib
     return lib
@@ -219,3 +225,72 @@ def backward_weight_m(dy, bufs, x_hat=None, dw=None, dw_dtype=torch.bfloat16):
                                             _dev(x_hat, torch.bfloat16, 2), _dev(dw, dw_dtype, 2),
                                             _SB_DTYPE[dw_dtype], _ptr(bufs.ws_dw), bufs.ws_dw.numel(), _stream()))
     return dw, x_hat
+
+
+# ---- SwitchBackQ: row-wise / column-wise weight quantization ---------------------------------------------------
+
+def quantize_colwise_transpose(w, q_t=None, state=None, ws=None):
+    """One absmax per column of w [rows, cols]; returns (q_t int8 [cols, rows], state f32 [cols])."""
+    lib = load_library()
+    rows, cols = w.shape
+    q_t = torch.empty((cols, rows), dtype=torch.int8, device=w.device) if q_t is None else q_t
+    state = torch.empty(cols, dtype=torch.float32, device=w.device) if state is None else state
+    ws = _workspace(SB_OP_QUANTIZE_COLWISE, 0, cols, rows, w.device) if ws is None else ws
+    _check(lib.switchback_quantize_colwise_transpose(_dev(w, torch.bfloat16, 2), rows, cols, _dev(q_t, torch.int8, 2),
+                                                     _dev(state, torch.float32), _ptr(ws), ws.numel(), _stream()))
+    return q_t, state
+
+
+def matmul_int8_dequant_rc(aq, state_a, bq, state_b, out_dtype=torch.bfloat16, out=None):
+    """out[i,j] = state_a[i] * state_b[j] / 127^2 * sum_k aq[i,k] bq[j,k]."""
+    lib = load_library()
+    M, K = aq.shape
+    N = bq.shape[0]
+    if bq.shape[1] != K:
+        raise SwitchBackError("contraction lengths differ")
+    out = torch.empty((M, N), dtype=out_dtype, device=aq.device) if out is None else out
+    _check(lib.switchback_matmul_int8_dequant_rc(_dev(aq, torch.int8, 2), _dev(state_a, torch.float32),
+                                                 _dev(bq, torch.int8, 2), _dev(state_b, torch.float32), M, N, K,
+                                                 _dev(out, out_dtype, 2), _SB_DTYPE[out_dtype], _stream()))
+    return out
+
+
+class LayerBuffersQ:
+    """Device buffers of one SwitchBackQ layer of shape (b, n, m): codes and states of both passes."""
+
+    def __init__(self, b, n, m, device="cuda"):
+        self.b, self.n, self.m = b, n, m
+        e = lambda shape, dt: torch.empty(shape, dtype=dt, device=device)
+        self.xq, self.state_x = e((b, n), torch.int8), e((b,), torch.float32)
+        self.wq, self.state_w_row = e((m, n), torch.int8), e((m,), torch.float32)
+        self.gq, self.state_g = e((b, m), torch.int8), e((b,), torch.float32)
+        self.wq_t, self.state_w_col = e((n, m), torch.int8), e((n,), torch.float32)
+        self.ws = _workspace(SB_OP_QUANTIZE_COLWISE, 0, n, m, device)
+
+
+def forward_q(x, w, bufs=None, y=None, y_dtype=torch.bfloat16):
+    """SwitchBackQ forward.  Returns (y [b,m], bufs)."""
+    lib = load_library()
+    b, n = x.shape
+    m = w.shape[0]
+    if w.shape[1] != n:
+        raise SwitchBackError("x [b,n] and w [m,n] disagree on n")
+    bufs = LayerBuffersQ(b, n, m, x.device) if bufs is None else bufs
+    y = torch.empty((b, m), dtype=y_dtype, device=x.device) if y is None else y
+    _check(lib.switchback_forward_q(_dev(x, torch.bfloat16, 2), _dev(w, torch.bfloat16, 2), b, n, m,
+                                    _dev(y, y_dtype, 2), _SB_DTYPE[y_dtype], _ptr(bufs.xq), _ptr(bufs.state_x),
+                                    _ptr(bufs.wq), _ptr(bufs.state_w_row), _stream()))
+    return y, bufs
+
+
+def backward_input_q(dy, w, bufs, dx=None, dx_dtype=torch.bfloat16):
+    """SwitchBackQ input gradient.  Returns dx [b,n]; fills bufs.gq, state_g, wq_t, state_w_col."""
+    lib = load_library()
+    b, m = dy.shape
+    n = w.shape[1]
+    dx = torch.empty((b, n), dtype=dx_dtype, device=dy.device) if dx is None else dx
+    _check(lib.switchback_backward_input_q(_dev(dy, torch.bfloat16, 2), _dev(w, torch.bfloat16, 2), b, n, m,
+                                           _dev(dx, dx_dtype, 2), _SB_DTYPE[dx_dtype], _ptr(bufs.gq),
+                                           _ptr(bufs.state_g), _ptr(bufs.wq_t), _ptr(bufs.state_w_col),
+                                           _ptr(bufs.ws), bufs.ws.numel(), _stream()))
+    return dx

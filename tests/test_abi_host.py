@@ -46,6 +46,8 @@ def test_workspace_sizes(lib):
     big = sb.workspace_bytes(sb.SB_OP_BACKWARD_WEIGHT, 32896, 1280, 1280)
     assert big % (1280 * 1280 * 4) == 0          # whole binary32 partial matrices
     assert sb.workspace_bytes(sb.SB_OP_BACKWARD_WEIGHT, 16384, 4096, 16384) == 0  # enough tiles, no split
+    assert sb.workspace_bytes(sb.SB_OP_QUANTIZE_COLWISE, 0, 1280, 5120) == 64 * 1280 * 2   # 64 row runs of 16-bit maxima
+    assert sb.workspace_bytes(sb.SB_OP_QUANTIZE_COLWISE, 0, 64, 32) == 2 * 64 * 2
     assert sb.workspace_bytes(99, 1, 64, 64) == 0
 
 
@@ -77,6 +79,16 @@ def test_bad_arguments_are_rejected_before_launch(lib):
     assert lib.switchback_backward_input(fake, sp, 8, 64, 96, fake, 0, fake, fake, null) == SHAPE
     assert lib.switchback_backward_input(null, sp, 8, 64, 64, fake, 0, fake, fake, null) == INVALID
     assert lib.switchback_backward_input(null, sp, 0, 64, 64, null, 0, null, null, null) == 0   # b = 0
+    assert lib.switchback_quantize_colwise_transpose(fake, 64, 64, fake, fake, fake, 16, null) == WS
+    assert lib.switchback_quantize_colwise_transpose(fake, 64, 72, fake, fake, fake, 1 << 20, null) == SHAPE
+    assert lib.switchback_quantize_colwise_transpose(fake, 64, 64, odd, fake, fake, 1 << 20, null) == INVALID
+    assert lib.switchback_matmul_int8_dequant_rc(fake, fake, fake, fake, 8, 64, 32, fake, 0, null) == SHAPE
+    assert lib.switchback_matmul_int8_dequant_rc(fake, fake, fake, null, 8, 64, 64, fake, 0, null) == INVALID
+    assert lib.switchback_matmul_int8_dequant_rc(fake, fake, fake, fake, 8, 64, 64, fake, 2, null) == INVALID
+    assert lib.switchback_forward_q(fake, fake, 8, 100, 64, fake, 0, fake, fake, fake, fake, null) == SHAPE
+    assert lib.switchback_forward_q(fake, fake, 8, 64, 64, fake, 0, fake, fake, null, fake, null) == INVALID
+    assert lib.switchback_backward_input_q(fake, fake, 8, 64, 64, fake, 0, fake, fake, fake, fake, fake, 8, null) == WS
+    assert lib.switchback_backward_input_q(fake, null, 8, 64, 64, fake, 0, fake, fake, fake, fake, fake, 1 << 20, null) == INVALID
     assert lib.switchback_dequantize_rowwise(fake, fake, 4, 60, fake, null) == SHAPE
     assert lib.switchback_dequantize_rowwise(fake, null, 4, 64, fake, null) == INVALID
     assert lib.switchback_dequantize_rowwise(null, null, 0, 64, null, null) == 0          # empty input: no-op

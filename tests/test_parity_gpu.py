@@ -187,6 +187,92 @@ def test_switchback_m_weight_gradient(oracle, shape):
 
 
 # ---------------------------------------------------------------------------------------------------------------
+# SwitchBackQ: column-wise quantize-transpose (bit-exact), row-and-column dequantization, the two int8 passes
+# ---------------------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("rows,cols", [(1024, 256), (16, 16), (64, 64), (272, 144), (1280, 5120), (5120, 1280),
+                                       (144, 4096 + 16)])
+def test_quantize_colwise_transpose(oracle, rows, cols):
+    rng = np.random.default_rng(rows * 3 + cols)
+    w = rand_bf16(rng, (rows, cols), 0.05)
+    w[:, 0] = 0                                                # an all-zero column
+    w[:, cols // 2] = I.f32_to_bf16_bits(I.bf16_bits_to_f32(w[:, cols // 2]) * np.float32(256.0))
+    q_t, s = sb.quantize_colwise_transpose(to_dev(w))
+    torch.cuda.synchronize()
+    qo, so = oracle.quantize_colwise_transpose(w)
+    np.testing.assert_array_equal(host(s).view(np.uint32), so.view(np.uint32))
+    np.testing.assert_array_equal(host(q_t), qo)
+
+
+@pytest.mark.parametrize("M,N,K", [(300, 320, 192), (512, 256, 1024), (257, 64, 128)])
+def test_rowcol_dequantized_product(oracle, M, N, K):
+    rng = np.random.default_rng(M + N + K)
+    a = rng.integers(-127, 128, size=(M, K)).astype(np.int8)
+    b = rng.integers(-127, 128, size=(N, K)).astype(np.int8)
+    sa = (np.abs(rng.standard_normal(M)) + 0.01).astype(np.float32)
+    sbv = (np.abs(rng.standard_normal(N)) * 0.1 + 0.001).astype(np.float32)
+    sa[M // 2] = 0.0
+    sbv[3] = 0.0
+    args = (torch.from_numpy(a).to(DEV), torch.from_numpy(sa).to(DEV), torch.from_numpy(b).to(DEV),
+            torch.from_numpy(sbv).to(DEV))
+    y32 = host(sb.matmul_int8_dequant_rc(*args, out_dtype=torch.float32))
+    ybf = bits_of(sb.matmul_int8_dequant_rc(*args, out_dtype=torch.bfloat16))
+    ref = oracle.dequantize_rowcol(oracle.matmul_int8(a, b), sa, sbv)
+    assert np.all(np.abs(y32 - ref) <= ulp(ref))
+    assert not y32[M // 2].any() and not y32[:, 3].any()
+    assert_bf16_is_rounding_within_one_ulp(ybf, ref, oracle)
+
+
+def check_layer_q(oracle, d, rows=None):
+    x, w, dy = to_dev(d["x"]), to_dev(d["w"]), to_dev(d["dy"])
+    y32, bufs = sb.forward_q(x, w, y_dtype=torch.float32)
+    ybf, _ = sb.forward_q(x, w, bufs=bufs, y_dtype=torch.bfloat16)
+    dx32 = sb.backward_input_q(dy, w, bufs, dx_dtype=torch.float32)
+    dxbf = sb.backward_input_q(dy, w, bufs, dx_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    xq, sx = oracle.quantize_rowwise(d["x"])
+    wq, sw = oracle.quantize_rowwise(d["w"])
+    gq, sg = oracle.quantize_rowwise(d["dy"])
+    wq_t, swc = oracle.quantize_colwise_transpose(d["w"])
+    for got, want in ((bufs.xq, xq), (bufs.wq, wq), (bufs.gq, gq), (bufs.wq_t, wq_t)):
+        np.testing.assert_array_equal(host(got), want)
+    for got, want in ((bufs.state_x, sx), (bufs.state_w_row, sw), (bufs.state_g, sg), (bufs.state_w_col, swc)):
+        np.testing.assert_array_equal(host(got).view(np.uint32), want.view(np.uint32))
+    rows = np.arange(d["x"].shape[0]) if rows is None else rows
+    idx = torch.from_numpy(rows).to(DEV)
+    ref = oracle.dequantize_rowcol(oracle.matmul_int8(xq[rows], wq), sx[rows], sw)
+    assert np.all(np.abs(host(y32[idx]) - ref) <= ulp(ref))
+    assert_bf16_is_rounding_within_one_ulp(bits_of(ybf[idx]), ref, oracle)
+    ref = oracle.dequantize_rowcol(oracle.matmul_int8(gq[rows], wq_t), sg[rows], swc)
+    assert np.all(np.abs(host(dx32[idx]) - ref) <= ulp(ref))
+    assert_bf16_is_rounding_within_one_ulp(bits_of(dxbf[idx]), ref, oracle)
+
+
+def test_switchback_q_tiny_with_edge_rows(oracle):
+    d = I.make_layer_inputs("tiny")
+    I.plant_edge_rows(d["x"])
+    I.plant_edge_rows(d["dy"])
+    d["w"][7] = 0                                              # an all-zero output feature
+    check_layer_q(oracle, d)
+
+
+@pytest.mark.parametrize("b,n,m", [(33, 192, 320), (300, 128, 576), (1000, 64, 256)])
+def test_switchback_q_ragged_shapes(oracle, b, n, m):
+    rng = np.random.default_rng(b + n + m + 1)
+    d = dict(x=rand_bf16(rng, (b, n)), w=rand_bf16(rng, (m, n), n ** -0.5), dy=rand_bf16(rng, (b, m), 0.1))
+    check_layer_q(oracle, d)
+
+
+@pytest.mark.parametrize("config,layer", [("vit_h14", 2), ("vit_h14", 3)])
+def test_switchback_q_full_size_sampled(oracle, config, layer):
+    L = I.CONFIGS[config].layers[layer]
+    d = I.make_layer_inputs(config, layer)
+    rng = np.random.default_rng(23)
+    rows = np.unique(np.concatenate([[0, 255, 256, L.b - 257, L.b - 1], rng.integers(0, L.b, 16)]))
+    check_layer_q(oracle, d, rows)
+
+
+# ---------------------------------------------------------------------------------------------------------------
 # the layer: tiny config, everything compared in full
 # ---------------------------------------------------------------------------------------------------------------
 
