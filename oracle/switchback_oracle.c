@@ -200,6 +200,39 @@ void sbo_weight_grad(const uint16_t *dy, const uint16_t *x, int64_t b, int64_t n
     }
 }
 
+/* ---- StableAdamW (the optimizer algorithm of the paper: AdamW with the debiasing folded into the decay rates and
+ * the learning rate divided by max(1, RMS_t), RMS_t^2 = mean(g^2 / u_t), taken per tensor) -------------------------
+ * One step for one tensor, in binary64 throughout; the state arrays are binary32 and are read, updated and written
+ * back (each stored value is the binary32 rounding of the binary64 result).  Per the implementation note of the
+ * appendix the denominator of the RMS is max(u_t, eps^2).  grad may be given as bf16 patterns (g16) or binary32
+ * (g32); exactly one of the two is non-NULL.  Returns RMS_t.
+ *   b1 = beta1 * (1 - beta1^(t-1)) / (1 - beta1^t),  b2 likewise
+ *   v = b1 v + (1 - b1) g ;  u = b2 u + (1 - b2) g^2
+ *   eta = alpha / max(1, RMS_t) ;  theta = theta - eta lambda theta - eta v / (sqrt(u) + eps)            */
+double sbo_stable_adamw_step(float *theta, float *v, float *u, const uint16_t *g16, const float *g32, int64_t count,
+                             double alpha, double beta1, double beta2, double eps, double lambda, int64_t t) {
+    const double b1 = beta1 * (1.0 - pow(beta1, (double)(t - 1))) / (1.0 - pow(beta1, (double)t));
+    const double b2 = beta2 * (1.0 - pow(beta2, (double)(t - 1))) / (1.0 - pow(beta2, (double)t));
+    double sum = 0.0;
+    for (int64_t j = 0; j < count; ++j) { /* sequential: the sum is part of the definition, keep one order */
+        const double g = g16 ? (double)bf16_to_f32(g16[j]) : (double)g32[j];
+        const double vj = b1 * (double)v[j] + (1.0 - b1) * g;
+        const double uj = b2 * (double)u[j] + (1.0 - b2) * g * g;
+        v[j] = (float)vj;
+        u[j] = (float)uj;
+        const double den = uj > eps * eps ? uj : eps * eps;
+        sum += g * g / den;
+    }
+    const double rms = count > 0 ? sqrt(sum / (double)count) : 0.0;
+    const double eta = alpha / (rms > 1.0 ? rms : 1.0);
+    for (int64_t j = 0; j < count; ++j) {
+        const double th = (double)theta[j];
+        /* the moments as stored (binary32), which is what a later step would see */
+        theta[j] = (float)(th - eta * lambda * th - eta * (double)v[j] / (sqrt((double)u[j]) + eps));
+    }
+    return rms;
+}
+
 int sbo_num_threads(void) {
 #ifdef _OPENMP
     return omp_get_max_threads();

@@ -36,6 +36,7 @@ def _load():
         _lib = ctypes.CDLL(_LIB)
         _lib.sbo_matmul_int8.restype = ctypes.c_int
         _lib.sbo_num_threads.restype = ctypes.c_int
+        _lib.sbo_stable_adamw_step.restype = ctypes.c_double
     return _lib
 
 
@@ -213,3 +214,22 @@ def backward_weight(dy, x):
     dw64 = weight_grad(dy, x)
     dw32 = dw64.astype(np.float32)
     return dict(dw64=dw64, dw32=dw32, dw_bf16=round_to_bf16(dw32))
+
+
+def stable_adamw_step(theta, v, u, grad, alpha, beta1, beta2, eps, lam, t):
+    """One StableAdamW step for one tensor (the optimizer algorithm of the paper), binary64 arithmetic on binary32
+    state.  grad: uint16 bf16 patterns or float32.  Returns (theta, v, u, rms) as new arrays."""
+    theta = np.array(theta, dtype=np.float32).ravel().copy()
+    v = np.array(v, dtype=np.float32).ravel().copy()
+    u = np.array(u, dtype=np.float32).ravel().copy()
+    grad = np.ascontiguousarray(grad).ravel()
+    assert theta.size == v.size == u.size == grad.size
+    g16 = _p(grad) if grad.dtype == np.uint16 else None
+    g32 = None
+    if g16 is None:
+        grad = grad.astype(np.float32)
+        g32 = _p(grad)
+    d = ctypes.c_double
+    rms = _load().sbo_stable_adamw_step(_p(theta), _p(v), _p(u), g16, g32, _i64(theta.size), d(alpha), d(beta1),
+                                        d(beta2), d(eps), d(lam), _i64(t))
+    return theta, v, u, float(rms)

@@ -476,3 +476,93 @@ def test_switchback_q_layer_bounds(oracle):
         + 64 * dg_[:, None] * dc_[None, :]
     assert np.all(np.abs(g["dx32"] - refx) <= boundx + 1e-5 * np.abs(refx) + 1e-30)
     np.testing.assert_array_equal(g["dx_bf16"], oracle.round_to_bf16(g["dx32"]))
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# StableAdamW (the optimizer algorithm: AdamW + update clipping by max(1, RMS_t))
+# ---------------------------------------------------------------------------------------------------------------
+
+def test_stable_adamw_first_step_closed_form(oracle):
+    """At t = 1 both corrected decay rates are 0, so v = g, u = g^2, RMS = 1 (for |g| > eps) and
+    theta_1 = theta_0 (1 - alpha lambda) - alpha g / (|g| + eps)."""
+    rng = np.random.default_rng(51)
+    th0 = rng.standard_normal(500).astype(np.float32)
+    g = (rng.standard_normal(500) * 0.01).astype(np.float32)
+    g[np.abs(g) < 1e-4] = 1e-4
+    th, v, u, rms = oracle.stable_adamw_step(th0, np.zeros(500), np.zeros(500), g, 1e-3, 0.9, 0.98, 1e-6, 0.2, 1)
+    np.testing.assert_array_equal(v, g)
+    np.testing.assert_allclose(u, g.astype(np.float64) ** 2, rtol=1e-7)
+    assert abs(rms - 1.0) < 1e-9
+    want = th0.astype(np.float64) * (1 - 1e-3 * 0.2) - 1e-3 * g.astype(np.float64) / (np.abs(g.astype(np.float64)) + 1e-6)
+    # theta is stored in binary32: half an ulp at |theta| < 4 is 1.2e-7, plus the rounding of u
+    np.testing.assert_allclose(th, want, rtol=0, atol=3e-7)
+
+
+def test_stable_adamw_equals_textbook_adamw_when_rms_is_small(oracle):
+    """With the correction folded into the decay rates, v_t and u_t are the bias-corrected moments of textbook Adam
+    (the footnote to the algorithm); as long as RMS_t <= 1 the step is textbook AdamW.  Five steps, binary64 NumPy."""
+    rng = np.random.default_rng(52)
+    n, a, b1, b2, eps, lam = 300, 2e-3, 0.9, 0.95, 1e-6, 0.1
+    th = rng.standard_normal(n).astype(np.float32)
+    v = np.zeros(n, np.float32)
+    u = np.zeros(n, np.float32)
+    m_ref, s_ref, th_ref = np.zeros(n), np.zeros(n), th.astype(np.float64)
+    base = rng.standard_normal(n) * 0.05
+    for t in range(1, 6):
+        g = (base * (1.0 - 0.1 * t)).astype(np.float32)        # shrinking gradients keep g^2/u below 1 on average
+        th, v, u, rms = oracle.stable_adamw_step(th, v, u, g, a, b1, b2, eps, lam, t)
+        gd = g.astype(np.float64)
+        m_ref = b1 * m_ref + (1 - b1) * gd
+        s_ref = b2 * s_ref + (1 - b2) * gd * gd
+        mh, sh = m_ref / (1 - b1 ** t), s_ref / (1 - b2 ** t)
+        np.testing.assert_allclose(v, mh, rtol=2e-6, atol=1e-9)
+        np.testing.assert_allclose(u, sh, rtol=2e-6, atol=1e-12)
+        assert rms <= 1.0 + 1e-6
+        th_ref = th_ref - a * lam * th_ref - a * mh / (np.sqrt(sh) + eps)
+        np.testing.assert_allclose(th, th_ref, rtol=0, atol=2e-6)
+
+
+def test_stable_adamw_clips_the_update_when_the_second_moment_is_stale(oracle):
+    """A gradient ten times larger than the history makes RMS_t > 1; the learning rate must then be alpha / RMS_t, and
+    RMS_t is the root mean of g^2 / max(u_t, eps^2) over the tensor (implementation note of the appendix)."""
+    rng = np.random.default_rng(53)
+    n, a, b1, b2, eps = 400, 1e-3, 0.9, 0.99, 1e-6
+    th = np.zeros(n, np.float32)
+    v = (rng.standard_normal(n) * 0.01).astype(np.float32)
+    u = (np.full(n, 1e-4) * rng.uniform(0.5, 2.0, n)).astype(np.float32)
+    g = (rng.standard_normal(n) * 0.1).astype(np.float32)
+    g[:7] = 0.0
+    v[:7] = 0.0
+    u[:7] = 0.0                                                  # dead coordinates: u_t = 0 -> eps^2 in the denominator
+    t = 50
+    th1, v1, u1, rms = oracle.stable_adamw_step(th, v, u, g, a, b1, b2, eps, 0.0, t)
+    b2h = b2 * (1 - b2 ** (t - 1)) / (1 - b2 ** t)
+    un = b2h * u.astype(np.float64) + (1 - b2h) * g.astype(np.float64) ** 2
+    want_rms = np.sqrt(np.mean(g.astype(np.float64) ** 2 / np.maximum(un, eps * eps)))
+    assert rms > 2.0 and abs(rms - want_rms) < 1e-9 * want_rms
+    eta = a / rms
+    np.testing.assert_allclose(th1, -eta * v1.astype(np.float64) / (np.sqrt(u1.astype(np.float64)) + eps), rtol=1e-6,
+                               atol=1e-12)
+    assert not th1[:7].any()                                     # dead coordinates do not move
+    # zero gradient, zero weight decay: parameters only move by the momentum term, moments decay
+    th2, v2, u2, rms2 = oracle.stable_adamw_step(th1, v1, u1, np.zeros(n, np.float32), a, b1, b2, eps, 0.0, t + 1)
+    assert rms2 == 0.0
+    b1h = b1 * (1 - b1 ** t) / (1 - b1 ** (t + 1))
+    np.testing.assert_allclose(v2, b1h * v1.astype(np.float64), rtol=1e-6)
+
+
+def test_stable_adamw_is_invariant_to_gradient_scale(oracle):
+    """Adam's update does not change when every gradient is multiplied by a constant (up to eps): neither may the RMS
+    nor the parameters."""
+    rng = np.random.default_rng(54)
+    n = 200
+    th0 = rng.standard_normal(n).astype(np.float32)
+    gs = [(rng.standard_normal(n) * 0.02).astype(np.float32) for _ in range(4)]
+    outs = []
+    for c in (1.0, 64.0):
+        th, v, u = th0.copy(), np.zeros(n, np.float32), np.zeros(n, np.float32)
+        for t, g in enumerate(gs, 1):
+            th, v, u, rms = oracle.stable_adamw_step(th, v, u, g * np.float32(c), 1e-3, 0.9, 0.98, 1e-12, 0.0, t)
+        outs.append((th, rms))
+    np.testing.assert_allclose(outs[0][0], outs[1][0], rtol=0, atol=2e-6)
+    assert abs(outs[0][1] - outs[1][1]) < 1e-6
