@@ -50,7 +50,8 @@ typedef enum {
     SB_OP_FORWARD = 1,
     SB_OP_BACKWARD_INPUT = 2,
     SB_OP_BACKWARD_WEIGHT = 3,
-    SB_OP_QUANTIZE_COLWISE = 4 /* also the workspace of switchback_backward_input_q; pass rows as m, cols as n */
+    SB_OP_QUANTIZE_COLWISE = 4, /* also the workspace of switchback_backward_input_q; pass rows as m, cols as n */
+    SB_OP_STABLE_ADAMW = 5      /* shape arguments ignored */
 } sb_op;
 
 /* What the forward pass leaves for the backward pass (Algorithm 1 saves X and W in 16 bit and re-quantizes W in
@@ -151,6 +152,24 @@ int switchback_forward_q(const void *x_bf16, const void *w_bf16, int64_t b, int6
 int switchback_backward_input_q(const void *dy_bf16, const void *w_bf16, int64_t b, int64_t n, int64_t m, void *dx,
                                 sb_dtype dx_dtype, int8_t *gq, float *state_g, int8_t *wq_t, float *state_w_col,
                                 void *ws, size_t ws_bytes, void *stream);
+
+/* One StableAdamW step for one parameter tensor (the optimizer algorithm of the paper's section on loss spikes: AdamW
+ * with the debiasing folded into the decay rates and update clipping; the implementation note of the appendix gives
+ * the guarded denominator of RMS_t).  With b1 = beta1 (1 - beta1^(t-1)) / (1 - beta1^t) and b2 likewise (formed on the
+ * host in binary64, then rounded to binary32; t = 1 gives 0):
+ *     v <- b1 v + (1 - b1) g,   u <- b2 u + (1 - b2) g^2,
+ *     RMS_t = sqrt(mean_j(g_j^2 / max(u_j, eps^2))) over the `count` elements of this tensor,
+ *     eta = alpha / max(1, RMS_t),   theta <- theta - eta lambda theta - eta v / (sqrt(u) + eps).
+ * Arithmetic is binary32 per element; the mean is accumulated in binary64 in a fixed order (deterministic).
+ *   theta, v, u: [count] f32 device arrays, updated in place (v, u start at zero before step 1);
+ *   grad: [count] device array, SB_BF16 or SB_F32 (grad_dtype), read only; all four 16-byte aligned;
+ *   t >= 1 is the step number; 0 <= beta1, beta2 < 1; eps > 0; alpha is the scheduled learning rate of this step;
+ *   rms_out: optional device float that receives RMS_t (NULL to skip);
+ *   ws: SB_OP_STABLE_ADAMW workspace (partial sums; scratch).  count == 0 is a no-op.
+ * Tensors of one model are independent calls (the clipping is per tensor, as in the paper). */
+int switchback_stable_adamw_step(float *theta, float *v, float *u, const void *grad, sb_dtype grad_dtype,
+                                 int64_t count, float alpha, float beta1, float beta2, float eps, float lambda,
+                                 int64_t t, float *rms_out, void *ws, size_t ws_bytes, void *stream);
 
 /* Bytes of device workspace `op` needs for a layer of this shape (0 if none).  Shape arguments an op does not
  * use are ignored (for SB_OP_QUANTIZE_TENSORWISE pass rows as m and cols as n). */

@@ -46,7 +46,14 @@ size_t gemm_bf16_tn_workspace_bytes(int64_t b, int64_t n, int64_t m);
 hipError_t launch_gemm_bf16_tn(const void *dy, const void *x, int64_t b, int64_t n, int64_t m, void *dw,
                                sb_dtype dw_dtype, void *ws, hipStream_t stream);
 
+size_t stable_adamw_workspace_bytes();
+// b1_hat / b2_hat are the corrected decay rates, omb1 / omb2 their complements to one (all formed by the caller).
+hipError_t launch_stable_adamw_step(float *theta, float *v, float *u, const void *grad, bool grad_bf16, int64_t count,
+                                    float alpha, float b1_hat, float b2_hat, float omb1, float omb2, float eps,
+                                    float lambda, float *rms_out, void *ws, hipStream_t stream);
+
 constexpr int kTensorwisePartials = 1024;  // upper bound on blocks of the tensor-wise absmax pass
+constexpr int kAdamwPartials = 2048;  // upper bound on the workgroups of a StableAdamW step
 constexpr int kColwiseRuns = 64;  // upper bound on the row runs of the column-wise absmax pass
 
 }  // namespace sb

@@ -2,6 +2,8 @@
 // (arxiv 2304.13013).  Every step runs in the HIP kernels of this library; nothing here touches tensor data.
 #include "sb_common.h"
 
+#include <cmath>
+
 namespace {
 
 constexpr int64_t kMaxIntK = 131072;  // 127^2 * K < 2^31 needs K <= 133143; rounded down to a power of two
@@ -211,6 +213,28 @@ int switchback_backward_input_q(const void *dy_bf16, const void *w_bf16, int64_t
     return from_hip(sb::launch_gemm_i8_dequant(gq, state_g, wq_t, nullptr, state_w_col, b, n, m, dx, dx_dtype, s));
 }
 
+int switchback_stable_adamw_step(float *theta, float *v, float *u, const void *grad, sb_dtype grad_dtype,
+                                 int64_t count, float alpha, float beta1, float beta2, float eps, float lambda,
+                                 int64_t t, float *rms_out, void *ws, size_t ws_bytes, void *stream) {
+    if (count < 0 || t < 1) return SB_INVALID_ARG;
+    if (grad_dtype != SB_BF16 && grad_dtype != SB_F32) return SB_INVALID_ARG;
+    if (!(beta1 >= 0.0f && beta1 < 1.0f) || !(beta2 >= 0.0f && beta2 < 1.0f) || !(eps > 0.0f)) return SB_INVALID_ARG;
+    if (!std::isfinite(alpha) || !std::isfinite(lambda)) return SB_INVALID_ARG;
+    if (count == 0) return SB_OK;
+    if (!ok_ptr(theta) || !ok_ptr(v) || !ok_ptr(u) || !ok_ptr(grad) || ws == nullptr || !aligned16(ws))
+        return SB_INVALID_ARG;
+    if (ws_bytes < sb::stable_adamw_workspace_bytes()) return SB_WORKSPACE_TOO_SMALL;
+    // Corrected decay rates of the algorithm, in binary64: beta (1 - beta^(t-1)) / (1 - beta^t); 0 at t = 1.
+    auto corrected = [](double beta, int64_t step) {
+        if (beta == 0.0) return 0.0;
+        return beta * (1.0 - std::pow(beta, (double)(step - 1))) / (1.0 - std::pow(beta, (double)step));
+    };
+    const double b1 = corrected((double)beta1, t), b2 = corrected((double)beta2, t);
+    return from_hip(sb::launch_stable_adamw_step(theta, v, u, grad, grad_dtype == SB_BF16, count, alpha, (float)b1,
+                                                 (float)b2, (float)(1.0 - b1), (float)(1.0 - b2), eps, lambda, rms_out,
+                                                 ws, static_cast<hipStream_t>(stream)));
+}
+
 size_t switchback_workspace_bytes(int op, int64_t b, int64_t n, int64_t m) {
     switch (op) {
         case SB_OP_QUANTIZE_TENSORWISE:
@@ -222,6 +246,7 @@ size_t switchback_workspace_bytes(int op, int64_t b, int64_t n, int64_t m) {
         case SB_OP_QUANTIZE_COLWISE:  // w is [m, n]
             if (n <= 0 || m <= 0) return 0;
             return sb::quantize_colwise_workspace_bytes(m, n);
+        case SB_OP_STABLE_ADAMW: return sb::stable_adamw_workspace_bytes();
         default: return 0;
     }
 }

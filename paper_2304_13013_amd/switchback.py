@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libswitchback.so")
 
 SB_BF16, SB_F32, SB_I32_RAW = 0, 1, 2
 SB_OP_QUANTIZE_TENSORWISE, SB_OP_FORWARD, SB_OP_BACKWARD_INPUT, SB_OP_BACKWARD_WEIGHT, SB_OP_QUANTIZE_COLWISE = 0, 1, 2, 3, 4
+SB_OP_STABLE_ADAMW = 5
 
 _TORCH_DTYPE = {SB_BF16: torch.bfloat16, SB_F32: torch.float32, SB_I32_RAW: torch.int32}
 _SB_DTYPE = {v: k for k, v in _TORCH_DTYPE.items()}
@@ -55,6 +56,8 @@ def load_library():
     lib.switchback_matmul_int8_dequant_rc.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, ci, vp]
     lib.switchback_forward_q.argtypes = [vp, vp, i64, i64, i64, vp, ci, vp, vp, vp, vp, vp]
     lib.switchback_backward_input_q.argtypes = [vp, vp, i64, i64, i64, vp, ci, vp, vp, vp, vp, vp, sz, vp]
+    cf = ctypes.c_float
+    lib.switchback_stable_adamw_step.argtypes = [vp, vp, vp, vp, ci, i64, cf, cf, cf, cf, cf, i64, vp, vp, sz, vp]
     lib.switchback_workspace_bytes.argtypes = [ci, i64, i64, i64]
     lib.switchback_workspace_bytes.restype = sz
     lib.switchback_status_string.argtypes = [ci]
@@ -63,7 +66,7 @@ def load_library():
                  "switchback_forward", "switchback_backward_input", "switchback_backward_weight",
                  "switchback_dequantize_rowwise", "switchback_backward_weight_m",
                  "switchback_quantize_colwise_transpose", "switchback_matmul_int8_dequant_rc",
-                 "switchback_forward_q", "switchback_backward_input_q"):
+                 "switchback_forward_q", "switchback_backward_input_q", "switchback_stable_adamw_step"):
         getattr(lib, name).restype = ci
     _lib = lib
     return lib
@@ -294,3 +297,22 @@ def backward_input_q(dy, w, bufs, dx=None, dx_dtype=torch.bfloat16):
                                            _ptr(bufs.state_g), _ptr(bufs.wq_t), _ptr(bufs.state_w_col),
                                            _ptr(bufs.ws), bufs.ws.numel(), _stream()))
     return dx
+
+
+def stable_adamw_step(theta, v, u, grad, alpha, beta1, beta2, eps, lam, t, rms_out=None, ws=None):
+    """One StableAdamW step for one tensor, in place on theta, v, u (f32, any shape, contiguous); grad bf16 or f32.
+    Returns rms_out (a 1-element f32 device tensor holding RMS_t)."""
+    lib = load_library()
+    count = theta.numel()
+    for name, x in (("theta", theta), ("v", v), ("u", u)):
+        _dev(x, torch.float32)
+        if x.numel() != count:
+            raise SwitchBackError("%s has %d elements, expected %d" % (name, x.numel(), count))
+    if grad.dtype not in (torch.bfloat16, torch.float32) or grad.numel() != count:
+        raise SwitchBackError("grad must be bf16 or f32 with as many elements as theta")
+    rms_out = torch.empty(1, dtype=torch.float32, device=theta.device) if rms_out is None else rms_out
+    ws = _workspace(SB_OP_STABLE_ADAMW, 0, 0, 0, theta.device) if ws is None else ws
+    _check(lib.switchback_stable_adamw_step(_ptr(theta), _ptr(v), _ptr(u), _dev(grad, grad.dtype),
+                                            _SB_DTYPE[grad.dtype], count, alpha, beta1, beta2, eps, lam, t,
+                                            _ptr(rms_out), _ptr(ws), ws.numel(), _stream()))
+    return rms_out

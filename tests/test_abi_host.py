@@ -48,6 +48,7 @@ def test_workspace_sizes(lib):
     assert sb.workspace_bytes(sb.SB_OP_BACKWARD_WEIGHT, 16384, 4096, 16384) == 0  # enough tiles, no split
     assert sb.workspace_bytes(sb.SB_OP_QUANTIZE_COLWISE, 0, 1280, 5120) == 64 * 1280 * 2   # 64 row runs of 16-bit maxima
     assert sb.workspace_bytes(sb.SB_OP_QUANTIZE_COLWISE, 0, 64, 32) == 2 * 64 * 2
+    assert sb.workspace_bytes(sb.SB_OP_STABLE_ADAMW, 0, 0, 0) == 2048 * 8                  # binary64 partial sums
     assert sb.workspace_bytes(99, 1, 64, 64) == 0
 
 
@@ -97,6 +98,15 @@ def test_bad_arguments_are_rejected_before_launch(lib):
     assert lib.switchback_backward_weight(fake, fake, 8, 64, 64, fake, 2, fake, 1 << 30, null) == INVALID
     assert lib.switchback_backward_weight(fake, fake, 32896, 1280, 1280, fake, 0, fake, 64, null) == WS
     assert lib.switchback_backward_weight(fake, fake, 8, 64, 64, null, 0, fake, 1 << 30, null) == INVALID
+    adam = lib.switchback_stable_adamw_step
+    good = (1e-3, 0.9, 0.98, 1e-6, 0.2)
+    assert adam(fake, fake, fake, fake, 0, 100, *good, 0, null, fake, 1 << 20, null) == INVALID    # t starts at 1
+    assert adam(fake, fake, fake, fake, 2, 100, *good, 1, null, fake, 1 << 20, null) == INVALID    # grad dtype
+    assert adam(fake, fake, fake, fake, 0, 100, 1e-3, 1.0, 0.98, 1e-6, 0.2, 1, null, fake, 1 << 20, null) == INVALID
+    assert adam(fake, fake, fake, fake, 0, 100, 1e-3, 0.9, 0.98, 0.0, 0.2, 1, null, fake, 1 << 20, null) == INVALID
+    assert adam(fake, odd, fake, fake, 0, 100, *good, 1, null, fake, 1 << 20, null) == INVALID
+    assert adam(fake, fake, fake, fake, 0, 100, *good, 1, null, fake, 8, null) == WS
+    assert adam(null, null, null, null, 0, 0, *good, 1, null, null, 0, null) == 0                  # empty tensor
 
 
 def test_binding_refuses_cpu_tensors():

@@ -413,3 +413,93 @@ def test_layer_full_size_sampled(oracle, config, layer):
     dwm_ref = oracle.weight_grad(np.ascontiguousarray(d["dy"][:, jrows]), xh)
     got = host(dwm[torch.from_numpy(jrows).to(DEV)]).astype(np.float64)
     assert np.abs(got - dwm_ref).max() <= 1e-2 * float(np.sqrt((dwm_ref ** 2).mean()))
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# StableAdamW (the optimizer algorithm of the paper; per-tensor update clipping)
+# ---------------------------------------------------------------------------------------------------------------
+
+def adamw_case(count, seed, grad_bf16, first_step, spike):
+    """Seeded optimizer state in the ranges of a transformer weight matrix mid-training: |theta| ~ 0.02, gradients
+    ~ 1e-3 with a few exact zeros (dead coordinates keep u = v = 0), u ~ E[g^2]; `spike` multiplies the gradient by
+    30 so that RMS_t > 1 and the learning rate is clipped."""
+    rng = np.random.default_rng(seed)
+    theta = (rng.standard_normal(count) * 0.02).astype(np.float32)
+    g = (rng.standard_normal(count) * 1e-3 * (30.0 if spike else 1.0)).astype(np.float32)
+    if first_step:
+        v = np.zeros(count, np.float32)
+        u = np.zeros(count, np.float32)
+    else:
+        v = (rng.standard_normal(count) * 3e-4).astype(np.float32)
+        u = (rng.uniform(0.3, 3.0, count) * 1e-6).astype(np.float32)
+    dead = rng.random(count) < 0.01
+    g[dead] = 0.0
+    v[dead] = 0.0
+    u[dead] = 0.0
+    if grad_bf16:
+        g = I.f32_to_bf16_bits(g)
+    return theta, v, u, g
+
+
+# The C ABI takes the hyper-parameters as binary32; the oracle gets the same binary32 values (1 - 0.98f differs from
+# 1 - 0.98 by 1e-6 relative, which is an input difference, not arithmetic).
+ADAMW_HYPER = {k: float(np.float32(x)) for k, x in dict(alpha=2e-3, beta1=0.9, beta2=0.98, eps=1e-6, lam=0.2).items()}
+
+
+def check_adamw(oracle, count, seed, grad_bf16, t, spike=False):
+    h = ADAMW_HYPER
+    theta, v, u, g = adamw_case(count, seed, grad_bf16, t == 1, spike)
+    th_o, v_o, u_o, rms_o = oracle.stable_adamw_step(theta, v, u, g, h["alpha"], h["beta1"], h["beta2"], h["eps"],
+                                                     h["lam"], t)
+    th_d, v_d, u_d = (torch.from_numpy(a.copy()).to(DEV) for a in (theta, v, u))
+    g_d = to_dev(g) if grad_bf16 else torch.from_numpy(g).to(DEV)
+    rms_d = sb.stable_adamw_step(th_d, v_d, u_d, g_d, h["alpha"], h["beta1"], h["beta2"], h["eps"], h["lam"], t)
+    torch.cuda.synchronize()
+    rms = float(rms_d.item())
+    assert abs(rms - rms_o) <= 2e-6 * rms_o + 1e-30, (rms, rms_o)
+    if spike:
+        assert rms_o > 2.0
+    # Tolerances from the arithmetic: binary32 multiply-adds (2^-24 relative per rounding, decay rates rounded once).
+    gf = (g.astype(np.uint32) << 16).view(np.float32).astype(np.float64) if grad_bf16 else g.astype(np.float64)
+    b1 = h["beta1"] * (1 - h["beta1"] ** (t - 1)) / (1 - h["beta1"] ** t)
+    e = 2.0 ** -24
+    tol_v = 4 * e * (np.abs(b1 * v.astype(np.float64)) + np.abs((1 - b1) * gf)) + 1e-44
+    assert (np.abs(host(v_d).astype(np.float64) - v_o) <= tol_v).all()
+    assert (np.abs(host(u_d).astype(np.float64) - u_o) <= 8 * e * u_o.astype(np.float64) + 1e-44).all()
+    eta = h["alpha"] / max(1.0, rms_o)
+    den = np.sqrt(u_o.astype(np.float64)) + h["eps"]
+    tol_th = (2 * np.spacing(np.abs(th_o)).astype(np.float64) + eta * tol_v / den
+              + 4e-6 * np.abs(eta * v_o.astype(np.float64) / den) + 1e-6 * np.abs(eta * h["lam"] * theta))
+    err = np.abs(host(th_d).astype(np.float64) - th_o)
+    assert (err <= tol_th).all(), "theta off by up to %.3g (tolerance ratio %.2f)" % (err.max(), (err / tol_th).max())
+    return err, tol_th
+
+
+@pytest.mark.parametrize("count", [1, 3, 5, 1023, 4096, 4097, 70001, 1280 * 1280])
+@pytest.mark.parametrize("grad_bf16", [True, False])
+def test_stable_adamw_step(oracle, count, grad_bf16):
+    check_adamw(oracle, count, 1000 + count % 997, grad_bf16, t=1)
+    check_adamw(oracle, count, 2000 + count % 997, grad_bf16, t=7)
+    check_adamw(oracle, count, 3000 + count % 997, grad_bf16, t=300, spike=True)
+
+
+def test_stable_adamw_full_size_weight_and_grid_stride(oracle):
+    """The benchmark's tensor (one MLP weight of ViT-H/14, 1280 x 5120) and one large enough that every workgroup
+    loops (the grid is capped), with a count that leaves a tail."""
+    check_adamw(oracle, 1280 * 5120, 77, True, t=12)
+    check_adamw(oracle, 1280 * 5120, 78, False, t=12, spike=True)
+    check_adamw(oracle, 20 * 1000 * 1000 + 3, 79, True, t=5)
+
+
+def test_stable_adamw_is_deterministic_and_leaves_grad_alone():
+    theta, v, u, g = adamw_case(300001, 5, True, False, True)
+    outs = []
+    for _ in range(2):
+        th_d, v_d, u_d = (torch.from_numpy(a.copy()).to(DEV) for a in (theta, v, u))
+        g_d = to_dev(g)
+        rms = sb.stable_adamw_step(th_d, v_d, u_d, g_d, 1e-3, 0.9, 0.95, 1e-6, 0.1, 9)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(bits_of(g_d), g)
+        outs.append((host(th_d), host(v_d), host(u_d), host(rms)))
+    for a, b in zip(*outs):
+        np.testing.assert_array_equal(a.view(np.uint32), b.view(np.uint32))
