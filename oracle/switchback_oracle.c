@@ -233,6 +233,150 @@ double sbo_stable_adamw_step(float *theta, float *v, float *u, const uint16_t *g
     return rms;
 }
 
+/* ---- float8 SwitchBack (the "float8" paragraph of Section 2.2.1: the int8 code path with
+ * round(127 x / absmax(x)) replaced by float8cast(x / absmax(x)); the 8-bit float types are those of the format paper it
+ * cites: E4M3 = 1 sign, 4 exponent (bias 7), 3 mantissa bits, no infinities, largest finite 448, subnormals m * 2^-9;
+ * E5M2 = 1/5/2, bias 15, IEEE-like, largest finite 57344, subnormals m * 2^-16) ---------------------------------------
+ * fmt: 0 = E4M3, 1 = E5M2.  Codes travel as bytes, sign in bit 7. */
+
+static void f8_shape(int fmt, int *mbits, int *bias, double *max_finite) {
+    if (fmt == 0) { *mbits = 3; *bias = 7; *max_finite = 448.0; }
+    else          { *mbits = 2; *bias = 15; *max_finite = 57344.0; }
+}
+
+/* float8cast: the representable value nearest to x, ties to the even mantissa; magnitudes beyond the largest finite
+ * value saturate to it (cannot happen for |x| <= 1, the only inputs the layer produces).  NaN is out of contract. */
+static uint8_t f8_encode(float x, int fmt) {
+    int mbits, bias;
+    double maxf;
+    f8_shape(fmt, &mbits, &bias, &maxf);
+    const uint8_t sign = signbit(x) ? 0x80u : 0u;
+    double a = fabs((double)x);
+    if (a == 0.0) return sign;
+    int e;
+    (void)frexp(a, &e);                 /* a = f * 2^e, f in [0.5, 1)  ->  a = 1.xxx * 2^(e-1) */
+    int E = e - 1;
+    const int emin = 1 - bias;          /* exponent of the smallest normal; subnormals share its spacing */
+    if (E < emin) E = emin;
+    const double step = ldexp(1.0, E - mbits);
+    double r = nearbyint(a / step) * step;   /* a/step is exact; nearbyint = round-half-to-even (default mode) */
+    if (r > maxf) r = maxf;
+    if (r == 0.0) return sign;
+    if (r < ldexp(1.0, emin)) return (uint8_t)(sign | (unsigned)(r / ldexp(1.0, emin - mbits)));
+    (void)frexp(r, &e);
+    E = e - 1;
+    const unsigned mant = (unsigned)((r / ldexp(1.0, E) - 1.0) * (double)(1 << mbits));
+    return (uint8_t)(sign | ((unsigned)(E + bias) << mbits) | mant);
+}
+
+static double f8_decode(uint8_t code, int fmt) {
+    int mbits, bias;
+    double maxf;
+    f8_shape(fmt, &mbits, &bias, &maxf);
+    const unsigned mant = code & ((1u << mbits) - 1u), ef = (code & 0x7fu) >> mbits;
+    double v = ef == 0 ? ldexp((double)mant, 1 - bias - mbits)
+                       : ldexp(1.0 + (double)mant / (double)(1 << mbits), (int)ef - bias);
+    return (code & 0x80u) ? -v : v;     /* the NaN / infinity codes are never produced by f8_encode */
+}
+
+void sbo_float8_encode(const float *x, int64_t count, int fmt, uint8_t *codes) {
+    for (int64_t i = 0; i < count; ++i) codes[i] = f8_encode(x[i], fmt);
+}
+
+void sbo_float8_decode(const uint8_t *codes, int64_t count, int fmt, double *out) {
+    for (int64_t i = 0; i < count; ++i) out[i] = f8_decode(codes[i], fmt);
+}
+
+/* The scale of the float8 path: t = fl(1/s), formed first like the int8 path forms fl(127/s); zero rows and rows
+ * whose 1/s overflows binary32 quantize to zeros with state 0. */
+static float f8_scale_from_absmax(float s, float *stored_state) {
+    float t = 1.0f / s;
+    if (s == 0.0f || !isfinite(t)) {
+        *stored_state = 0.0f;
+        return 0.0f;
+    }
+    *stored_state = s;
+    return t;
+}
+
+/* Row-wise: codes[i,j] = float8cast(fl(x[i,j] * fl(1/absmax_i))), state[i] = absmax_i. */
+void sbo_quantize_rowwise_f8(const uint16_t *x, int64_t rows, int64_t cols, int fmt, uint8_t *codes, float *state) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < rows; ++i) {
+        const uint16_t *xi = x + i * cols;
+        float s = 0.0f;
+        for (int64_t j = 0; j < cols; ++j) {
+            float a = fabsf(bf16_to_f32(xi[j]));
+            if (a > s) s = a;
+        }
+        const float t = f8_scale_from_absmax(s, &state[i]);
+        for (int64_t j = 0; j < cols; ++j) {
+            const float p = bf16_to_f32(xi[j]) * t;
+            codes[i * cols + j] = f8_encode(p, fmt);
+        }
+    }
+}
+
+/* Tensor-wise: one absmax for the matrix; codes [rows,cols] and the transposed copy codes_t [cols,rows] (may be NULL). */
+void sbo_quantize_tensorwise_f8(const uint16_t *w, int64_t rows, int64_t cols, int fmt, uint8_t *codes,
+                                uint8_t *codes_t, float *state) {
+    float s = 0.0f;
+    for (int64_t e = 0; e < rows * cols; ++e) {
+        float a = fabsf(bf16_to_f32(w[e]));
+        if (a > s) s = a;
+    }
+    const float t = f8_scale_from_absmax(s, &state[0]);
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < rows; ++i)
+        for (int64_t j = 0; j < cols; ++j) {
+            const float p = bf16_to_f32(w[i * cols + j]) * t;
+            const uint8_t c = f8_encode(p, fmt);
+            codes[i * cols + j] = c;
+            if (codes_t) codes_t[j * rows + i] = c;
+        }
+}
+
+/* acc[i,j] = sum_k value(a[i,k]) * value(b[j,k]), exactly: every product is a multiple of 2^-25 below 2^32 in
+ * magnitude for |values| <= 448 x 57344, and for the layer's |values| <= 1 the partial sums stay far inside the
+ * 53-bit significand, so the binary64 sum has no rounding and no order.  abs_acc (may be NULL) receives
+ * sum_k |a| |b|, the quantity error bounds of a lower-precision summation are stated in. */
+void sbo_matmul_f8(const uint8_t *a, int fmt_a, const uint8_t *b, int fmt_b, int64_t M, int64_t N, int64_t K,
+                   double *acc, double *abs_acc) {
+    double ta[256], tb[256];
+    for (int c = 0; c < 256; ++c) {
+        ta[c] = f8_decode((uint8_t)c, fmt_a);
+        tb[c] = f8_decode((uint8_t)c, fmt_b);
+    }
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M; ++i)
+        for (int64_t j = 0; j < N; ++j) {
+            double sum = 0.0, asum = 0.0;
+            for (int64_t k = 0; k < K; ++k) {
+                const double pr = ta[a[i * K + k]] * tb[b[j * K + k]];
+                sum += pr;
+                asum += fabs(pr);
+            }
+            acc[i * N + j] = sum;
+            if (abs_acc) abs_acc[i * N + j] = asum;
+        }
+}
+
+/* Dequantization of the float8 product: the forward equation without the 1/127^2 (the codes already lie in [-1, 1]):
+ * r_i = fl(state_row[i] * state_tensor) in binary32 like the int8 path, y = acc * r_i rounded once to binary32 from
+ * the exact binary64 product (y64 keeps it unrounded). */
+void sbo_dequantize_f8(const double *acc, int64_t M, int64_t N, const float *state_row, float state_tensor, float *y32,
+                       double *y64) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M; ++i) {
+        const float r = state_row[i] * state_tensor;
+        for (int64_t j = 0; j < N; ++j) {
+            const double y = acc[i * N + j] * (double)r;
+            if (y64) y64[i * N + j] = y;
+            y32[i * N + j] = (float)y;
+        }
+    }
+}
+
 int sbo_num_threads(void) {
 #ifdef _OPENMP
     return omp_get_max_threads();

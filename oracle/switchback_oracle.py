@@ -233,3 +233,85 @@ def stable_adamw_step(theta, v, u, grad, alpha, beta1, beta2, eps, lam, t):
     rms = _load().sbo_stable_adamw_step(_p(theta), _p(v), _p(u), g16, g32, _i64(theta.size), d(alpha), d(beta1),
                                         d(beta2), d(eps), d(lam), _i64(t))
     return theta, v, u, float(rms)
+
+
+E4M3, E5M2 = 0, 1
+
+
+def float8_encode(x, fmt):
+    """float8cast of binary32 values: uint8 codes of the nearest representable value (ties to even)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    codes = np.empty(x.shape, np.uint8)
+    _load().sbo_float8_encode(_p(x), _i64(x.size), ctypes.c_int(fmt), _p(codes))
+    return codes
+
+
+def float8_decode(codes, fmt):
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    out = np.empty(codes.shape, np.float64)
+    _load().sbo_float8_decode(_p(codes), _i64(codes.size), ctypes.c_int(fmt), _p(out))
+    return out
+
+
+def quantize_rowwise_f8(x, fmt):
+    """float8cast(x / absmax_row(x)): returns (codes uint8 [r,c], state f32 [r])."""
+    x = _bf16(x)
+    r, c = x.shape
+    codes = np.empty((r, c), np.uint8)
+    state = np.empty(r, np.float32)
+    _load().sbo_quantize_rowwise_f8(_p(x), _i64(r), _i64(c), ctypes.c_int(fmt), _p(codes), _p(state))
+    return codes, state
+
+
+def quantize_tensorwise_f8(w, fmt):
+    """float8cast(w / absmax(w)): returns (codes [r,c], codes_t [c,r], state f32)."""
+    w = _bf16(w)
+    r, c = w.shape
+    codes = np.empty((r, c), np.uint8)
+    codes_t = np.empty((c, r), np.uint8)
+    state = np.empty(1, np.float32)
+    _load().sbo_quantize_tensorwise_f8(_p(w), _i64(r), _i64(c), ctypes.c_int(fmt), _p(codes), _p(codes_t), _p(state))
+    return codes, codes_t, state[0]
+
+
+def matmul_f8(a, fmt_a, b, fmt_b, want_abs=False):
+    """Exact sum_k value(a[i,k]) value(b[j,k]) in binary64; with want_abs also sum_k |.||.|."""
+    a = np.ascontiguousarray(a, dtype=np.uint8)
+    b = np.ascontiguousarray(b, dtype=np.uint8)
+    M, K = a.shape
+    N, K2 = b.shape
+    assert K == K2
+    acc = np.empty((M, N), np.float64)
+    abs_acc = np.empty((M, N), np.float64) if want_abs else None
+    _load().sbo_matmul_f8(_p(a), ctypes.c_int(fmt_a), _p(b), ctypes.c_int(fmt_b), _i64(M), _i64(N), _i64(K), _p(acc),
+                          _p(abs_acc) if want_abs else None)
+    return (acc, abs_acc) if want_abs else acc
+
+
+def dequantize_f8(acc, state_row, state_tensor, want_f64=False):
+    acc = np.ascontiguousarray(acc, dtype=np.float64)
+    M, N = acc.shape
+    state_row = np.ascontiguousarray(state_row, dtype=np.float32)
+    y32 = np.empty((M, N), np.float32)
+    y64 = np.empty((M, N), np.float64) if want_f64 else None
+    _load().sbo_dequantize_f8(_p(acc), _i64(M), _i64(N), _p(state_row), ctypes.c_float(float(state_tensor)), _p(y32),
+                              _p(y64) if want_f64 else None)
+    return (y32, y64) if want_f64 else y32
+
+
+def forward_f8(x, w, fmt_x=E4M3, fmt_w=E4M3):
+    """float8 SwitchBack forward: Y = dequant(f8_row(X) f8_tensor(W)^T)."""
+    xq, state_x = quantize_rowwise_f8(x, fmt_x)
+    wq, wq_t, state_w = quantize_tensorwise_f8(w, fmt_w)
+    acc, abs_acc = matmul_f8(xq, fmt_x, wq, fmt_w, want_abs=True)
+    y32 = dequantize_f8(acc, state_x, state_w)
+    return dict(xq=xq, state_x=state_x, wq=wq, wq_t=wq_t, state_w=state_w, acc=acc, abs_acc=abs_acc, y32=y32,
+                y_bf16=round_to_bf16(y32))
+
+
+def backward_input_f8(dy, wq_t, state_w, fmt_g=E5M2, fmt_w=E4M3):
+    """float8 SwitchBack input gradient: dX = dequant(f8_row(dY) f8_tensor(W))."""
+    gq, state_g = quantize_rowwise_f8(dy, fmt_g)
+    acc, abs_acc = matmul_f8(gq, fmt_g, wq_t, fmt_w, want_abs=True)
+    dx32 = dequantize_f8(acc, state_g, state_w)
+    return dict(gq=gq, state_g=state_g, acc=acc, abs_acc=abs_acc, dx32=dx32, dx_bf16=round_to_bf16(dx32))

@@ -566,3 +566,153 @@ def test_stable_adamw_is_invariant_to_gradient_scale(oracle):
         outs.append((th, rms))
     np.testing.assert_allclose(outs[0][0], outs[1][0], rtol=0, atol=2e-6)
     assert abs(outs[0][1] - outs[1][1]) < 1e-6
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# float8 SwitchBack (the "float8" paragraph of Section 2.2.1: float8cast(x / absmax(x)))
+# ---------------------------------------------------------------------------------------------------------------
+
+F8_TORCH = {0: "float8_e4m3fn", 1: "float8_e5m2"}
+
+
+def f8_values(fmt):
+    """All finite non-negative values of the format, built here from the field definition (not the oracle's code)."""
+    mbits, bias = (3, 7) if fmt == 0 else (2, 15)
+    vals = []
+    for code in range(128):
+        ef, mant = code >> mbits, code & ((1 << mbits) - 1)
+        if fmt == 0 and code == 0x7F:
+            continue                                  # E4M3 NaN
+        if fmt == 1 and ef == 31:
+            continue                                  # E5M2 infinities / NaNs
+        vals.append((mant * 2.0 ** (1 - bias - mbits)) if ef == 0 else (1 + mant / 2 ** mbits) * 2.0 ** (ef - bias))
+    return np.array(vals)
+
+
+def test_float8_format_facts_from_the_cited_format_paper(oracle):
+    rows = [ln.split("#")[0].split() for ln in open(os.path.join(GOLDEN, "float8_formats.txt"))
+            if ln.strip() and not ln.startswith("#")]
+    assert len(rows) == 10
+    for name, code, value in rows:
+        fmt = {"E4M3": 0, "E5M2": 1}[name]
+        assert oracle.float8_decode(np.array([int(code, 16)], np.uint8), fmt)[0] == float(value)
+        assert oracle.float8_encode(np.array([float(value)], np.float32), fmt)[0] == int(code, 16)
+    for fmt in (0, 1):
+        vals = f8_values(fmt)
+        assert (np.diff(vals) > 0).all()
+        codes = np.array([c for c in range(128) if not (fmt == 0 and c == 0x7F) and not (fmt == 1 and c >= 0x7C)], np.uint8)
+        np.testing.assert_array_equal(oracle.float8_decode(codes, fmt), vals)
+        np.testing.assert_array_equal(oracle.float8_decode(codes | 0x80, fmt), -vals)
+
+
+@pytest.mark.parametrize("fmt", [0, 1])
+def test_float8cast_is_nearest_even_and_equals_an_independent_cast(oracle, fmt):
+    import torch
+    rng = np.random.default_rng(60 + fmt)
+    vals = f8_values(fmt)
+    mids = (vals[:-1] + vals[1:]) / 2                       # every tie of the format (exact in binary32)
+    x = np.concatenate([rng.standard_normal(20000) * 0.4, rng.standard_normal(20000) * 2.0 ** -8,
+                        rng.standard_normal(5000) * 2.0 ** -15, mids, -mids, vals, -vals,
+                        np.nextafter(mids.astype(np.float32), np.float32(0)), np.nextafter(mids.astype(np.float32), np.float32(1e9)),
+                        [0.0, -0.0, 1.0, -1.0, 1.0 + 2.0 ** -23, 1.0 - 2.0 ** -24]]).astype(np.float32)
+    x = x[np.abs(x) <= vals[-1]]
+    got = oracle.float8_encode(x, fmt)
+    # (1) torch's CPU cast, an independent library routine
+    ref = torch.from_numpy(x).to(getattr(torch, F8_TORCH[fmt])).view(torch.uint8).numpy()
+    np.testing.assert_array_equal(got, ref)
+    # (2) brute force: nearest value of the table; on a tie the one with the even code
+    a = np.abs(x.astype(np.float64))
+    d = np.abs(a[:, None] - vals[None, :])
+    best = d.min(axis=1)
+    dec = np.abs(oracle.float8_decode(got, fmt))
+    np.testing.assert_array_equal(np.abs(a - dec), best)
+    tie = (d == best[:, None]).sum(axis=1) == 2
+    assert tie.sum() >= len(mids)
+    assert ((got[tie] & 1) == 0).all()
+    assert ((got >> 7) == np.signbit(x)).all()
+
+
+@pytest.mark.parametrize("fmt", [0, 1])
+def test_float8_rowwise_quantization_properties(oracle, fmt):
+    rng = np.random.default_rng(62 + fmt)
+    x = I.f32_to_bf16_bits((rng.standard_normal((40, 256)) * rng.uniform(0.01, 30, (40, 1))).astype(np.float32))
+    x[5] = 0
+    codes, state = oracle.quantize_rowwise_f8(x, fmt)
+    xf = I.bf16_bits_to_f32(x).astype(np.float64)
+    absmax = np.abs(xf).max(axis=1)
+    np.testing.assert_array_equal(state, absmax.astype(np.float32))
+    assert not codes[5].any() and state[5] == 0
+    one = 0x38 if fmt == 0 else 0x3C
+    live = absmax > 0
+    # the absmax element maps to +-1.0, nothing exceeds it
+    assert (((codes & 0x7F).max(axis=1) == one) | ~live).all()
+    # half-spacing error bound of x / absmax: relative 2^-(mbits+1) for normals, absolute half a subnormal step
+    mbits, bias = (3, 7) if fmt == 0 else (2, 15)
+    u = xf[live] / absmax[live, None]
+    err = np.abs(oracle.float8_decode(codes[live], fmt) - u)
+    assert (err <= np.maximum(np.abs(u) * 2.0 ** -(mbits + 1), 2.0 ** (1 - bias - mbits - 1)) * (1 + 1e-6)).all()
+    # power-of-two scaling of a row changes the state only; negation flips the sign bit only
+    x4 = I.f32_to_bf16_bits((I.bf16_bits_to_f32(x) * np.float32(0.25)))
+    c4, s4 = oracle.quantize_rowwise_f8(x4, fmt)
+    np.testing.assert_array_equal(c4, codes)
+    np.testing.assert_array_equal(s4, state * np.float32(0.25))
+    cn, _ = oracle.quantize_rowwise_f8(x ^ np.uint16(0x8000), fmt)
+    np.testing.assert_array_equal(cn, codes ^ 0x80)
+    # rows made of format values times a power-of-two absmax are fixed points
+    vals = f8_values(fmt)
+    vals = vals[vals <= 1.0]
+    g = rng.choice(vals, (8, 64)) * rng.choice([-1.0, 1.0], (8, 64))
+    g[:, 0] = 1.0
+    gx = I.f32_to_bf16_bits((g * 2.0 ** rng.integers(-6, 6, (8, 1))).astype(np.float32))
+    cg, sg = oracle.quantize_rowwise_f8(gx, fmt)
+    np.testing.assert_array_equal(oracle.float8_decode(cg, fmt) * sg[:, None].astype(np.float64),
+                                  I.bf16_bits_to_f32(gx).astype(np.float64))
+    # tensor-wise = row-wise of the flattened matrix, and the transposed copy is the transpose
+    ct, ctt, st = oracle.quantize_tensorwise_f8(x, fmt)
+    cf, sf = oracle.quantize_rowwise_f8(x.reshape(1, -1), fmt)
+    np.testing.assert_array_equal(ct.reshape(1, -1), cf)
+    assert st == sf[0]
+    np.testing.assert_array_equal(ctt, ct.T)
+
+
+def test_float8_product_is_exact_and_the_layer_stays_within_the_format_error(oracle):
+    import torch
+    rng = np.random.default_rng(64)
+    a = rng.integers(0, 256, (37, 320)).astype(np.uint8)
+    b = rng.integers(0, 256, (29, 320)).astype(np.uint8)
+    a[(a & 0x7F) > 0x38] &= 0xB8                                   # keep |values| <= 1 like the layer does; no NaN codes
+    b[(b & 0x7F) > 0x3C] &= 0xBC
+    acc, abs_acc = oracle.matmul_f8(a, 0, b, 1, want_abs=True)
+    ta = torch.from_numpy(a).view(torch.float8_e4m3fn).to(torch.float64)
+    tb = torch.from_numpy(b).view(torch.float8_e5m2).to(torch.float64)
+    np.testing.assert_array_equal(acc, (ta @ tb.T).numpy())       # exact: any summation order gives the same bits
+    np.testing.assert_array_equal(abs_acc, (ta.abs() @ tb.abs().T).numpy())
+
+    # the layer: fixed-point inputs reproduce the true product; random inputs stay inside the format's error bound
+    vals = f8_values(0)
+    vals = vals[vals <= 1.0]
+    gx = rng.choice(vals, (16, 128)) * rng.choice([-1.0, 1.0], (16, 128))
+    gx[:, 3] = 1.0
+    gw = rng.choice(vals, (24, 128)) * rng.choice([-1.0, 1.0], (24, 128))
+    gw[7, 7] = -1.0
+    xb = I.f32_to_bf16_bits((gx * 2.0 ** rng.integers(-3, 4, (16, 1))).astype(np.float32))
+    wb = I.f32_to_bf16_bits((gw * 0.5).astype(np.float32))
+    f = oracle.forward_f8(xb, wb)
+    true = I.bf16_bits_to_f32(xb).astype(np.float64) @ I.bf16_bits_to_f32(wb).astype(np.float64).T
+    np.testing.assert_array_equal(f["y32"], true.astype(np.float32))
+
+    x = I.f32_to_bf16_bits(rng.standard_normal((48, 512)).astype(np.float32))
+    w = I.f32_to_bf16_bits((rng.standard_normal((40, 512)) / np.sqrt(512)).astype(np.float32))
+    dy = I.f32_to_bf16_bits((rng.standard_normal((48, 40)) * 0.1).astype(np.float32))
+    xf, wf, gf = (I.bf16_bits_to_f32(t).astype(np.float64) for t in (x, w, dy))
+    f = oracle.forward_f8(x, w)                                     # E4M3 x E4M3
+    ex = 2.0 ** -4 * np.abs(xf) + 2.0 ** -10 * np.abs(xf).max(axis=1, keepdims=True)
+    ew = 2.0 ** -4 * np.abs(wf) + 2.0 ** -10 * np.abs(wf).max()
+    bound = ex @ np.abs(wf).T + np.abs(xf) @ ew.T + ex @ ew.T
+    err = np.abs(f["y32"] - xf @ wf.T)
+    assert (err <= bound * (1 + 1e-6) + 1e-6).all() and err.max() > 0.01 * bound.max()
+    bi = oracle.backward_input_f8(dy, f["wq_t"], f["state_w"])      # E5M2 x E4M3
+    eg = 2.0 ** -3 * np.abs(gf) + 2.0 ** -17 * np.abs(gf).max(axis=1, keepdims=True)
+    bound = eg @ np.abs(wf) + np.abs(gf) @ ew + eg @ ew
+    err = np.abs(bi["dx32"] - gf @ wf)
+    assert (err <= bound * (1 + 1e-6) + 1e-6).all() and err.max() > 0.01 * bound.max()
