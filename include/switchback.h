@@ -153,6 +153,36 @@ int switchback_backward_input_q(const void *dy_bf16, const void *w_bf16, int64_t
                                 sb_dtype dx_dtype, int8_t *gq, float *state_g, int8_t *wq_t, float *state_w_col,
                                 void *ws, size_t ws_bytes, void *stream);
 
+/* The float8 variant of the layer (the "float8" paragraph of Section 2.2.1: the same code path with
+ * round(127 x / absmax(x)) replaced by float8cast(x / absmax(x)); the paper simulates it in 16 bit, here the codes are
+ * real 8-bit floats and the product runs on the float8 matrix instructions).  Formats are those of the format paper the
+ * section cites: SB_E4M3 (bias 7, no infinities, largest 448) and SB_E5M2 (bias 15, IEEE-like).  Codes are bytes with
+ * the sign in bit 7; they lie in [-1, 1], so the dequantization has no 1/127^2:
+ *   state = absmax (binary32), t = 1/state (one correctly rounded divide; zero or overflowing rows give zero codes and
+ *   state 0), code = float8cast(fl(x * t)) with round-to-nearest-even onto the format's values, subnormals included;
+ *   out[i,j] = (state_row[i] * state_tensor) * sum_k value(aq[i,k]) value(bq[j,k]), the sum accumulated in binary32
+ *   by the matrix instruction (order unspecified but deterministic), r_i = fl(state_row[i] * state_tensor) formed
+ *   first, output rounded to nearest-even when SB_BF16.
+ * Shapes as for the int8 calls, and additionally K % 128 == 0 (n % 128 == 0 and m % 128 == 0 for the layer calls);
+ * out_dtype SB_BF16 or SB_F32.  The layer calls use the int8 layer's sb_saved with its code buffers holding float8
+ * bytes (same sizes).  The weight gradient of the variant is switchback_backward_weight (16 bit). */
+typedef enum { SB_E4M3 = 0, SB_E5M2 = 1 } sb_f8_format;
+int switchback_quantize_rowwise_f8(const void *x_bf16, int64_t rows, int64_t cols, sb_f8_format fmt, uint8_t *codes,
+                                   float *state, void *stream);
+int switchback_quantize_tensorwise_f8(const void *w_bf16, int64_t rows, int64_t cols, sb_f8_format fmt, uint8_t *codes,
+                                      uint8_t *codes_t, float *state, void *ws, size_t ws_bytes, void *stream);
+int switchback_matmul_f8_dequant(const uint8_t *aq, sb_f8_format fmt_a, const float *state_row, const uint8_t *bq,
+                                 sb_f8_format fmt_b, const float *state_tensor, int64_t M, int64_t N, int64_t K,
+                                 void *out, sb_dtype out_dtype, void *stream);
+/* Y = dequant(f8_row(X) f8_tensor(W)^T); fills saved (xq, state_x in fmt_x; wq, wq_t, state_w in fmt_w). */
+int switchback_forward_f8(const void *x_bf16, const void *w_bf16, int64_t b, int64_t n, int64_t m, void *y,
+                          sb_dtype y_dtype, const sb_saved *saved, sb_f8_format fmt_x, sb_f8_format fmt_w, void *ws,
+                          size_t ws_bytes, void *stream);
+/* dX = dequant(f8_row(dY) f8_tensor(W)); reads saved->wq_t (fmt_w) and state_w; fills gq [b,m] (fmt_g), state_g [b]. */
+int switchback_backward_input_f8(const void *dy_bf16, const sb_saved *saved, int64_t b, int64_t n, int64_t m, void *dx,
+                                 sb_dtype dx_dtype, uint8_t *gq, float *state_g, sb_f8_format fmt_g,
+                                 sb_f8_format fmt_w, void *stream);
+
 /* One StableAdamW step for one parameter tensor (the optimizer algorithm of the paper's section on loss spikes: AdamW
  * with the debiasing folded into the decay rates and update clipping; the implementation note of the appendix gives
  * the guarded denominator of RMS_t).  With b1 = beta1 (1 - beta1^(t-1)) / (1 - beta1^t) and b2 likewise (formed on the

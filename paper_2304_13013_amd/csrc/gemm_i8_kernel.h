@@ -45,6 +45,10 @@
 namespace sb {
 
 enum { OUT_BF16 = 0, OUT_F32 = 1, OUT_I32 = 2 };
+// Arithmetic of the product.  MATH_I8: int8 codes, v_mfma_i32_32x32x32_i8, scale state_tensor/127^2.  MATH_F8 + 2*fw + fx:
+// 8-bit float codes (f = 0: E4M3, 1: E5M2; fw for the weight-side operand b, fx for the token-side operand a),
+// v_mfma_f32_32x32x64_f8f6f4 with binary32 accumulators, scale state_tensor (the codes already lie in [-1, 1]).
+enum { MATH_I8 = 0, MATH_F8 = 4 };
 
 template <int BK_, int STAGES_, int LOADERS_, int MT_LOADER_ = 4, int STORE_NT_ = 0>
 struct GemmI8Cfg {
@@ -154,11 +158,23 @@ __device__ __forceinline__ void wait_stage(int later) {
 // What one wave does: an (MT*32) x 64 part of the workgroup's tile, rows from wm0.  Every role runs the same
 // sequence of barriers.
 // COLSCALE: out[i,j] = (float)acc * fl(state_row[i] * fl(state_col[j] / 127^2)) instead of the tensor-wise scale.
-template <class C, int OUT, int MT, bool COLSCALE>
+//
+// The float8 product runs the same pipeline with one MFMA per 64 k-values: an operand fragment is then 32 bytes per
+// lane, fetched by the two 16-byte LDS reads that two consecutive int8 k-steps would issue.  Which 64 k-values a
+// lane's registers hold does not matter as long as both operands use the same assignment, which they do.
+template <class C, int OUT, int MT, bool COLSCALE, int MATH = MATH_I8>
 __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const int wave, const int wm0) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     typedef __attribute__((address_space(3))) void lds_void;
     constexpr int S = C::STAGES;
+    constexpr bool F8 = MATH >= MATH_F8;
+    constexpr int FMT_X = MATH & 1, FMT_W = (MATH >> 1) & 1;
+    constexpr int RPF = F8 ? 2 : 1;            // 16-byte LDS reads per operand fragment
+    constexpr int KKG = C::KK / RPF;           // MFMA k-step groups per stage
+    typedef typename std::conditional<F8, v16f, v16i>::type AccT;
+    typedef typename std::conditional<F8, v8i, v4i>::type FragT;
+    static_assert(!F8 || (OUT != OUT_I32 && !COLSCALE), "the float8 product has dequantized outputs and a tensor-wise weight state");
+    static_assert(KKG >= 2 && KKG % 2 == 0, "the register double-buffering alternates per k-step group within a stage");
     constexpr int NSCALE = OUT != OUT_I32 ? MT + (COLSCALE ? C::NT * 4 : 0) : 0;  // per-lane scale loads per tile
     constexpr int NFRAG = MT + C::NT;
     constexpr int EPI_STORES = MT * C::STORES_PER_BLOCK;  // 16-byte global stores per lane per tile
@@ -208,21 +224,32 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
     // MFMA operand fragments, double-buffered in registers.  A k-step group issues its MFMAs in the order
     // (x0,w0) (x0,w1) (x1,w0) (x1,w1) ... and reads the NEXT group's fragments in the order w0 x0 w1 x1 x2 x3 ..., one
     // read after each of its first MT+2 MFMAs.
-    v4i xf[2][MT], wf[2][C::NT];
+    FragT xf[2][MT], wf[2][C::NT];
     const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
     static_assert((C::BM + C::BN) * C::BK <= 65536, "fragment offsets must fit the 16-bit ds offset field");
     const unsigned x_off = wm0 * C::BK, w_off = (C::BM + wn0) * C::BK;
     // i-th fragment read of the group (stage in LDS slot `slot`, k-step kk) into register buffer buf.
     auto issue_frag_read = [&](int i, int buf, int slot, int kk) {
-        const unsigned at = lds_base + slot * C::STAGE_BYTES + frag_off[kk];
+        const unsigned at = lds_base + slot * C::STAGE_BYTES + frag_off[kk * RPF];
+        const unsigned at2 = lds_base + slot * C::STAGE_BYTES + frag_off[kk * RPF + RPF - 1];  // second half (float8)
+        auto read = [&](auto off, unsigned base) -> FragT {
+            constexpr int OFF = decltype(off)::value;
+            if constexpr (F8) {
+                const v4i lo = lds_read_b128<OFF>(at + base);
+                const v4i hi = lds_read_b128<OFF>(at2 + base);
+                return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            } else {
+                return lds_read_b128<OFF>(at + base);
+            }
+        };
         switch (i) {
-            case 0: wf[buf][0] = lds_read_b128<0>(at + w_off); break;
-            case 1: xf[buf][0] = lds_read_b128<0>(at + x_off); break;
-            case 2: wf[buf][1] = lds_read_b128<32 * C::BK>(at + w_off); break;
-            case 3: xf[buf][1] = lds_read_b128<32 * C::BK>(at + x_off); break;
-            case 4: xf[buf][2 % MT] = lds_read_b128<64 * C::BK>(at + x_off); break;
-            case 5: xf[buf][3 % MT] = lds_read_b128<96 * C::BK>(at + x_off); break;
-            default: xf[buf][4 % MT] = lds_read_b128<128 * C::BK>(at + x_off); break;
+            case 0: wf[buf][0] = read(std::integral_constant<int, 0>(), w_off); break;
+            case 1: xf[buf][0] = read(std::integral_constant<int, 0>(), x_off); break;
+            case 2: wf[buf][1] = read(std::integral_constant<int, 32 * C::BK>(), w_off); break;
+            case 3: xf[buf][1] = read(std::integral_constant<int, 32 * C::BK>(), x_off); break;
+            case 4: xf[buf][2 % MT] = read(std::integral_constant<int, 64 * C::BK>(), x_off); break;
+            case 5: xf[buf][3 % MT] = read(std::integral_constant<int, 96 * C::BK>(), x_off); break;
+            default: xf[buf][4 % MT] = read(std::integral_constant<int, 128 * C::BK>(), x_off); break;
         }
     };
     // Ties the register of the i-th fragment read to the wait that precedes this call.
@@ -237,8 +264,10 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
             default: asm volatile("" : "+v"(xf[buf][4 % MT])); break;
         }
     };
+    // n counts fragments; the counter counts reads.
+    static_assert(RPF * (MT + C::NT) <= 15, "lgkmcnt is a 4-bit counter");
     auto wait_lgkm_at_most = [&](int n) {
-        switch (n) {
+        switch (n * RPF) {
             case 0: wait_lgkmcnt<0>(); break;
             case 1: wait_lgkmcnt<1>(); break;
             case 2: wait_lgkmcnt<2>(); break;
@@ -246,7 +275,14 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
             case 4: wait_lgkmcnt<4>(); break;
             case 5: wait_lgkmcnt<5>(); break;
             case 6: wait_lgkmcnt<6>(); break;
-            default: wait_lgkmcnt<7>(); break;
+            case 7: wait_lgkmcnt<7>(); break;
+            case 8: wait_lgkmcnt<8>(); break;
+            case 9: wait_lgkmcnt<9>(); break;
+            case 10: wait_lgkmcnt<10>(); break;
+            case 11: wait_lgkmcnt<11>(); break;
+            case 12: wait_lgkmcnt<12>(); break;
+            case 13: wait_lgkmcnt<13>(); break;
+            default: wait_lgkmcnt<14>(); break;
         }
     };
 
@@ -256,7 +292,7 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
 
     // c = state_tensor / 127^2, read once (the pointer may alias nothing the kernel writes).
     float tensor_scale = 0.0f;
-    if (OUT != OUT_I32 && !COLSCALE) tensor_scale = p.state_tensor[0] / 16129.0f;
+    if (OUT != OUT_I32 && !COLSCALE) tensor_scale = F8 ? p.state_tensor[0] : p.state_tensor[0] / 16129.0f;
     asm volatile("" : "+v"(tensor_scale));
 
     // ---- Work list.  A segment is the k-tile range [kb, ke) of one output tile; segment i of this workgroup is the
@@ -345,7 +381,7 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
             }
         };
 #endif
-        v16i acc[MT][C::NT];
+        AccT acc[MT][C::NT];
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -402,8 +438,8 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
             constexpr bool last_stage = decltype(is_last_stage)::value;
             const int slot = g % S, next_slot = (g + 1) % S;
 #pragma unroll
-            for (int kk = 0; kk < C::KK; ++kk) {
-                const bool last_group = kk + 1 == C::KK;
+            for (int kk = 0; kk < KKG; ++kk) {
+                const bool last_group = kk + 1 == KKG;
                 const bool has_next = !last_group || !last_stage;  // another k-step group follows
                 const bool handed_over = last_group && has_next;
                 if (handed_over) {
@@ -440,7 +476,11 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
                         landed = need;
                     }
                     if (idx == 1) SB_STAMP_AT(kk * 3 + 1, kt * 4 + 0);
-                    acc[mt][nt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[cur][nt], xf[cur][mt], acc[mt][nt], 0, 0, 0);
+                    if constexpr (F8)
+                        acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wf[cur][nt], xf[cur][mt], acc[mt][nt],
+                                                                                      FMT_W, FMT_X, 0, 0, 0, 0);
+                    else
+                        acc[mt][nt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[cur][nt], xf[cur][mt], acc[mt][nt], 0, 0, 0);
                     if (idx < NFRAG && has_next) issue_frag_read(idx, nxt, read_slot, next_kk);
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -553,7 +593,7 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
                                 v4i v;
 #pragma unroll
                                 for (int e = 0; e < 4; ++e)
-                                    v[e] = acc[mt][nt][4 * q + e];
+                                    v[e] = (int)acc[mt][nt][4 * q + e];
                                 *reinterpret_cast<v4i *>(static_cast<int *>(p.out) + (int64_t)gr * p.N + gc) = v;
                             }
                         }
@@ -572,15 +612,15 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
 
 // The kernel body.  It is a __device__ template called from non-template __global__ entry points: a __global__
 // template that uses device-only buffer builtins does not instantiate in the host pass.
-template <class C, int OUT, bool COLSCALE = false>
+template <class C, int OUT, bool COLSCALE = false, int MATH = MATH_I8>
 __device__ __forceinline__ void gemm_i8_dequant_body(const GemmI8Args &p) {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform: what derives from it is scalar
     if (C::MT_LOADER == 4)
-        gemm_i8_dequant_role<C, OUT, 4, COLSCALE>(p, wave, (wave / C::WAVES_N) * C::WTM);
+        gemm_i8_dequant_role<C, OUT, 4, COLSCALE, MATH>(p, wave, (wave / C::WAVES_N) * C::WTM);
     else if (wave < C::LOADERS)
-        gemm_i8_dequant_role<C, OUT, C::MT_LOADER, COLSCALE>(p, wave, 0);
+        gemm_i8_dequant_role<C, OUT, C::MT_LOADER, COLSCALE, MATH>(p, wave, 0);
     else
-        gemm_i8_dequant_role<C, OUT, 8 - C::MT_LOADER, COLSCALE>(p, wave, C::MT_LOADER * 32);
+        gemm_i8_dequant_role<C, OUT, 8 - C::MT_LOADER, COLSCALE, MATH>(p, wave, C::MT_LOADER * 32);
 }
 
 // Launch geometry shared by the entry points: persistent grid, a multiple of the XCD count.

@@ -8,6 +8,11 @@
 // low byte is the two's-complement int8 code.  The product and the addition are separate roundings (the file is
 // compiled with contraction off), and binary32 subnormals are preserved (the default float mode of HIP kernels).
 //
+// The float8 variant of the layer (the "float8" paragraph of the same section: float8cast(x / absmax(x)) in place of
+// round(127 x / absmax(x))) runs through the same kernels with CODE = CODE_E4M3 or CODE_E5M2: the scale is
+// t = 1/absmax (one correctly rounded divide), each code is the hardware's round-to-nearest-even conversion
+// (v_cvt_pk_fp8_f32 / v_cvt_pk_bf8_f32, OCP formats on gfx950) of the rounded binary32 product x*t.
+//
 // All three kernels are HBM-bound: one 16-byte load per 8 elements, the row (or tile) stays in registers between
 // the absmax and the quantization, codes leave as 8- or 16-byte stores.
 #include "sb_common.h"
@@ -16,6 +21,8 @@ namespace sb {
 namespace {
 
 constexpr float kRoundMagic = 12582912.0f;  // 1.5 * 2^23
+
+enum { CODE_INT8 = 0, CODE_E4M3 = 1, CODE_E5M2 = 2 };
 
 __device__ __forceinline__ unsigned int pk_absmax_u16(unsigned int running, unsigned int two_bf16) {
     v2us a = __builtin_bit_cast(v2us, running);
@@ -41,9 +48,10 @@ __device__ __forceinline__ unsigned int wave_max_u32(unsigned int v) {
 
 // absmax bit pattern (15 bits) -> (scale t, stored state).  Zero rows and rows whose scale would overflow
 // binary32 quantize to zeros and store state 0.
+template <int CODE = CODE_INT8>
 __device__ __forceinline__ float scale_from_absmax_bits(unsigned int bits15, float *stored_state) {
     float s = bf16_bits_to_float(bits15);
-    float t = 127.0f / s;
+    float t = (CODE == CODE_INT8 ? 127.0f : 1.0f) / s;
     if (bits15 == 0u || __builtin_isinf(t)) {
         t = 0.0f;
         s = 0.0f;
@@ -58,8 +66,31 @@ __device__ __forceinline__ unsigned int code_bits(float x, float t) {
     return __float_as_uint(r);
 }
 
-// 8 bf16 (4 dwords, element 2d in the low half of dword d) -> 8 int8 codes (2 dwords).
+// 8 bf16 (4 dwords, element 2d in the low half of dword d) -> 8 one-byte codes (2 dwords).
+template <int CODE = CODE_INT8>
 __device__ __forceinline__ v2u quantize_chunk(v4u c, float t) {
+    if (CODE != CODE_INT8) {
+        const unsigned int d[4] = {c.x, c.y, c.z, c.w};
+        float p[8];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            p[2 * j] = __uint_as_float(d[j] << 16) * t;  // one rounding each
+            p[2 * j + 1] = __uint_as_float(d[j] & 0xffff0000u) * t;
+        }
+        int lo = 0, hi = 0;  // the conversion writes one 16-bit half of its destination and keeps the other
+        if (CODE == CODE_E4M3) {
+            lo = __builtin_amdgcn_cvt_pk_fp8_f32(p[0], p[1], lo, false);
+            lo = __builtin_amdgcn_cvt_pk_fp8_f32(p[2], p[3], lo, true);
+            hi = __builtin_amdgcn_cvt_pk_fp8_f32(p[4], p[5], hi, false);
+            hi = __builtin_amdgcn_cvt_pk_fp8_f32(p[6], p[7], hi, true);
+        } else {
+            lo = __builtin_amdgcn_cvt_pk_bf8_f32(p[0], p[1], lo, false);
+            lo = __builtin_amdgcn_cvt_pk_bf8_f32(p[2], p[3], lo, true);
+            hi = __builtin_amdgcn_cvt_pk_bf8_f32(p[4], p[5], hi, false);
+            hi = __builtin_amdgcn_cvt_pk_bf8_f32(p[6], p[7], hi, true);
+        }
+        return v2u{(unsigned int)lo, (unsigned int)hi};
+    }
     unsigned int r[8];
     r[0] = code_bits(__uint_as_float(c.x << 16), t);
     r[1] = code_bits(__uint_as_float(c.x & 0xffff0000u), t);
@@ -81,7 +112,7 @@ __device__ __forceinline__ v2u quantize_chunk(v4u c, float t) {
 }
 
 // ---- row-wise: one wavefront per row (cols <= 64*8*NCH) ---------------------------------------------------
-template <int NCH>
+template <int NCH, int CODE>
 __global__ __launch_bounds__(256) void quantize_rowwise_wave_kernel(const v4u *__restrict__ x, int64_t rows,
                                                                     int chunks, v2u *__restrict__ q,
                                                                     float *__restrict__ state) {
@@ -100,18 +131,18 @@ __global__ __launch_bounds__(256) void quantize_rowwise_wave_kernel(const v4u *_
     for (int i = 0; i < NCH; ++i) m = absmax_of_chunk(m, v[i]);
     m = wave_max_u32(max(m & 0xffffu, m >> 16));
     float s;
-    const float t = scale_from_absmax_bits(m, &s);
+    const float t = scale_from_absmax_bits<CODE>(m, &s);
     if (lane == 0) state[row] = s;
     v2u *qr = q + row * chunks;
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
         int c = lane + 64 * i;
-        if (c < chunks) qr[c] = quantize_chunk(v[i], t);
+        if (c < chunks) qr[c] = quantize_chunk<CODE>(v[i], t);
     }
 }
 
 // ---- row-wise: one 256-thread block per row (cols <= 256*8*NCH) ---------------------------------------------
-template <int NCH>
+template <int NCH, int CODE>
 __global__ __launch_bounds__(256) void quantize_rowwise_block_kernel(const v4u *__restrict__ x, int chunks,
                                                                      v2u *__restrict__ q,
                                                                      float *__restrict__ state) {
@@ -132,17 +163,18 @@ __global__ __launch_bounds__(256) void quantize_rowwise_block_kernel(const v4u *
     __syncthreads();
     m = max(max(wave_max[0], wave_max[1]), max(wave_max[2], wave_max[3]));
     float s;
-    const float t = scale_from_absmax_bits(m, &s);
+    const float t = scale_from_absmax_bits<CODE>(m, &s);
     if (threadIdx.x == 0) state[row] = s;
     v2u *qr = q + row * chunks;
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
         int c = threadIdx.x + 256 * i;
-        if (c < chunks) qr[c] = quantize_chunk(v[i], t);
+        if (c < chunks) qr[c] = quantize_chunk<CODE>(v[i], t);
     }
 }
 
 // ---- row-wise: very wide rows, two passes over the row (the second one hits L2) ---------------------------
+template <int CODE>
 __global__ __launch_bounds__(256) void quantize_rowwise_wide_kernel(const v4u *__restrict__ x, int chunks,
                                                                     v2u *__restrict__ q,
                                                                     float *__restrict__ state) {
@@ -156,10 +188,10 @@ __global__ __launch_bounds__(256) void quantize_rowwise_wide_kernel(const v4u *_
     __syncthreads();
     m = max(max(wave_max[0], wave_max[1]), max(wave_max[2], wave_max[3]));
     float s;
-    const float t = scale_from_absmax_bits(m, &s);
+    const float t = scale_from_absmax_bits<CODE>(m, &s);
     if (threadIdx.x == 0) state[row] = s;
     v2u *qr = q + row * chunks;
-    for (int c = threadIdx.x; c < chunks; c += 256) qr[c] = quantize_chunk(xr[c], t);
+    for (int c = threadIdx.x; c < chunks; c += 256) qr[c] = quantize_chunk<CODE>(xr[c], t);
 }
 
 // ---- tensor-wise pass 1: per-block partial absmax (bit patterns) --------------------------------------------
@@ -183,6 +215,7 @@ __global__ __launch_bounds__(256) void absmax_partial_kernel(const v4u *__restri
 constexpr int kTile = 128;
 constexpr int kTileStride = kTile + 16;  // bytes per LDS row (keeps 16-byte alignment, staggers banks)
 
+template <int CODE>
 __global__ __launch_bounds__(256) void quantize_tensorwise_kernel(const v4u *__restrict__ w, int rows, int cols,
                                                                   int8_t *__restrict__ q,
                                                                   int8_t *__restrict__ q_t,
@@ -198,7 +231,7 @@ __global__ __launch_bounds__(256) void quantize_tensorwise_kernel(const v4u *__r
     __syncthreads();
     m = max(max(wave_max[0], wave_max[1]), max(wave_max[2], wave_max[3]));
     float s;
-    const float t = scale_from_absmax_bits(m, &s);
+    const float t = scale_from_absmax_bits<CODE>(m, &s);
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) state[0] = s;
 
     const int r0 = blockIdx.y * kTile, c0 = blockIdx.x * kTile;
@@ -209,7 +242,7 @@ __global__ __launch_bounds__(256) void quantize_tensorwise_kernel(const v4u *__r
         const int lr = id >> 4, lc = (id & 15) << 3;  // local row, local first column of the 8-element chunk
         const int r = r0 + lr, c = c0 + lc;
         if (r < rows && c < cols) {
-            const v2u codes = quantize_chunk(w[(int64_t)r * chunks_per_row + (c >> 3)], t);
+            const v2u codes = quantize_chunk<CODE>(w[(int64_t)r * chunks_per_row + (c >> 3)], t);
             *reinterpret_cast<v2u *>(q + (int64_t)r * cols + c) = codes;
             if (q_t) {
 #pragma unroll
@@ -365,16 +398,16 @@ hipError_t launch_quantize_colwise_transpose(const void *w, int64_t rows, int64_
     return hipGetLastError();
 }
 
-hipError_t launch_quantize_rowwise(const void *x, int64_t rows, int64_t cols, int8_t *q, float *state,
-                                   hipStream_t stream) {
-    if (rows == 0) return hipSuccess;
+template <int CODE>
+hipError_t launch_quantize_rowwise_t(const void *x, int64_t rows, int64_t cols, void *q, float *state,
+                                     hipStream_t stream) {
     const int chunks = (int)(cols / 8);
     const v4u *xp = static_cast<const v4u *>(x);
-    v2u *qp = reinterpret_cast<v2u *>(q);
+    v2u *qp = static_cast<v2u *>(q);
     const unsigned int wave_grid = (unsigned int)((rows + 3) / 4), block_grid = (unsigned int)rows;
 #define SB_WAVE(N)                                                                                          \
-    quantize_rowwise_wave_kernel<N><<<wave_grid, 256, 0, stream>>>(xp, rows, chunks, qp, state)
-#define SB_BLOCK(N) quantize_rowwise_block_kernel<N><<<block_grid, 256, 0, stream>>>(xp, chunks, qp, state)
+    quantize_rowwise_wave_kernel<N, CODE><<<wave_grid, 256, 0, stream>>>(xp, rows, chunks, qp, state)
+#define SB_BLOCK(N) quantize_rowwise_block_kernel<N, CODE><<<block_grid, 256, 0, stream>>>(xp, chunks, qp, state)
     if (chunks <= 64) SB_WAVE(1);
     else if (chunks <= 128) SB_WAVE(2);
     else if (chunks <= 192) SB_WAVE(3);
@@ -384,14 +417,28 @@ hipError_t launch_quantize_rowwise(const void *x, int64_t rows, int64_t cols, in
     else if (chunks <= 1024) SB_BLOCK(4);
     else if (chunks <= 1536) SB_BLOCK(6);
     else if (chunks <= 2048) SB_BLOCK(8);
-    else quantize_rowwise_wide_kernel<<<block_grid, 256, 0, stream>>>(xp, chunks, qp, state);
+    else quantize_rowwise_wide_kernel<CODE><<<block_grid, 256, 0, stream>>>(xp, chunks, qp, state);
 #undef SB_WAVE
 #undef SB_BLOCK
     return hipGetLastError();
 }
 
-hipError_t launch_quantize_tensorwise(const void *w, int64_t rows, int64_t cols, int8_t *q, int8_t *q_t,
-                                      float *state, unsigned int *partials, hipStream_t stream) {
+hipError_t launch_quantize_rowwise(const void *x, int64_t rows, int64_t cols, int8_t *q, float *state,
+                                   hipStream_t stream) {
+    if (rows == 0) return hipSuccess;
+    return launch_quantize_rowwise_t<CODE_INT8>(x, rows, cols, q, state, stream);
+}
+
+hipError_t launch_quantize_rowwise_f8(const void *x, int64_t rows, int64_t cols, int fmt, uint8_t *codes, float *state,
+                                      hipStream_t stream) {
+    if (rows == 0) return hipSuccess;
+    return fmt == 0 ? launch_quantize_rowwise_t<CODE_E4M3>(x, rows, cols, codes, state, stream)
+                    : launch_quantize_rowwise_t<CODE_E5M2>(x, rows, cols, codes, state, stream);
+}
+
+template <int CODE>
+hipError_t launch_quantize_tensorwise_t(const void *w, int64_t rows, int64_t cols, int8_t *q, int8_t *q_t,
+                                        float *state, unsigned int *partials, hipStream_t stream) {
     const int64_t nchunks = rows * cols / 8;
     const v4u *wp = static_cast<const v4u *>(w);
     int nblocks = (int)((nchunks + 256 * 4 - 1) / (256 * 4));
@@ -402,9 +449,21 @@ hipError_t launch_quantize_tensorwise(const void *w, int64_t rows, int64_t cols,
     if (e != hipSuccess) return e;
     if (rows == 0 || cols == 0) return hipSuccess;
     dim3 grid((unsigned int)((cols + kTile - 1) / kTile), (unsigned int)((rows + kTile - 1) / kTile));
-    quantize_tensorwise_kernel<<<grid, 256, 0, stream>>>(wp, (int)rows, (int)cols, q, q_t, state, partials,
-                                                         nblocks);
+    quantize_tensorwise_kernel<CODE><<<grid, 256, 0, stream>>>(wp, (int)rows, (int)cols, q, q_t, state, partials,
+                                                               nblocks);
     return hipGetLastError();
+}
+
+hipError_t launch_quantize_tensorwise(const void *w, int64_t rows, int64_t cols, int8_t *q, int8_t *q_t,
+                                      float *state, unsigned int *partials, hipStream_t stream) {
+    return launch_quantize_tensorwise_t<CODE_INT8>(w, rows, cols, q, q_t, state, partials, stream);
+}
+
+hipError_t launch_quantize_tensorwise_f8(const void *w, int64_t rows, int64_t cols, int fmt, uint8_t *codes,
+                                         uint8_t *codes_t, float *state, unsigned int *partials, hipStream_t stream) {
+    int8_t *q = reinterpret_cast<int8_t *>(codes), *q_t = reinterpret_cast<int8_t *>(codes_t);
+    return fmt == 0 ? launch_quantize_tensorwise_t<CODE_E4M3>(w, rows, cols, q, q_t, state, partials, stream)
+                    : launch_quantize_tensorwise_t<CODE_E5M2>(w, rows, cols, q, q_t, state, partials, stream);
 }
 
 }  // namespace sb

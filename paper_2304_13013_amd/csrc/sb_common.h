@@ -8,6 +8,7 @@
 namespace sb {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef float v16f __attribute__((ext_vector_type(16)));
@@ -38,10 +39,19 @@ hipError_t launch_quantize_colwise_transpose(const void *w, int64_t rows, int64_
                                              void *partials, hipStream_t stream);
 hipError_t launch_quantize_tensorwise(const void *w, int64_t rows, int64_t cols, int8_t *q, int8_t *q_t,
                                       float *state, unsigned int *partials, hipStream_t stream);
+hipError_t launch_quantize_rowwise_f8(const void *x, int64_t rows, int64_t cols, int fmt, uint8_t *codes, float *state,
+                                      hipStream_t stream);
+hipError_t launch_quantize_tensorwise_f8(const void *w, int64_t rows, int64_t cols, int fmt, uint8_t *codes,
+                                         uint8_t *codes_t, float *state, unsigned int *partials, hipStream_t stream);
 // state_col == nullptr: tensor-wise weight state (state_tensor[0]); else one state per output column (SwitchBackQ).
 hipError_t launch_gemm_i8_dequant(const int8_t *aq, const float *state_row, const int8_t *bq,
                                   const float *state_tensor, const float *state_col, int64_t M, int64_t N,
                                   int64_t K, void *out, sb_dtype out_dtype, hipStream_t stream);
+// 8-bit float product (fmt 0: E4M3, 1: E5M2 per operand): out[i,j] = (state_row[i] * state_tensor[0]) * sum_k a b.
+// K % 128 == 0; out SB_BF16 or SB_F32.
+hipError_t launch_gemm_f8_dequant(const uint8_t *aq, int fmt_a, const float *state_row, const uint8_t *bq, int fmt_b,
+                                  const float *state_tensor, int64_t M, int64_t N, int64_t K, void *out,
+                                  sb_dtype out_dtype, hipStream_t stream);
 size_t gemm_bf16_tn_workspace_bytes(int64_t b, int64_t n, int64_t m);
 hipError_t launch_gemm_bf16_tn(const void *dy, const void *x, int64_t b, int64_t n, int64_t m, void *dw,
                                sb_dtype dw_dtype, void *ws, hipStream_t stream);

@@ -10,6 +10,7 @@ constexpr int64_t kMaxIntK = 131072;  // 127^2 * K < 2^31 needs K <= 133143; rou
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 bool ok_ptr(const void *p) { return p != nullptr && aligned16(p); }
+bool ok_f8(int f) { return f == SB_E4M3 || f == SB_E5M2; }
 bool ok_dtype(int d) { return d == SB_BF16 || d == SB_F32 || d == SB_I32_RAW; }
 
 int layer_shape_status(int64_t b, int64_t n, int64_t m) {
@@ -211,6 +212,91 @@ int switchback_backward_input_q(const void *dy_bf16, const void *w_bf16, int64_t
     e = sb::launch_quantize_rowwise(dy_bf16, b, m, gq, state_g, s);
     if (e != hipSuccess) return SB_HIP_ERROR;
     return from_hip(sb::launch_gemm_i8_dequant(gq, state_g, wq_t, nullptr, state_w_col, b, n, m, dx, dx_dtype, s));
+}
+
+int switchback_quantize_rowwise_f8(const void *x_bf16, int64_t rows, int64_t cols, sb_f8_format fmt, uint8_t *codes,
+                                   float *state, void *stream) {
+    if (rows < 0 || cols <= 0 || !ok_f8(fmt)) return SB_INVALID_ARG;
+    if (cols % 8 || cols > 65536 || rows > (int64_t)1 << 30) return SB_UNSUPPORTED_SHAPE;
+    if (rows == 0) return SB_OK;
+    if (!ok_ptr(x_bf16) || !ok_ptr(codes) || state == nullptr) return SB_INVALID_ARG;
+    return from_hip(sb::launch_quantize_rowwise_f8(x_bf16, rows, cols, fmt, codes, state,
+                                                   static_cast<hipStream_t>(stream)));
+}
+
+int switchback_quantize_tensorwise_f8(const void *w_bf16, int64_t rows, int64_t cols, sb_f8_format fmt, uint8_t *codes,
+                                      uint8_t *codes_t, float *state, void *ws, size_t ws_bytes, void *stream) {
+    if (rows <= 0 || cols <= 0 || !ok_f8(fmt)) return SB_INVALID_ARG;
+    if (rows % 16 || cols % 16 || rows > (int64_t)1 << 24 || cols > (int64_t)1 << 24) return SB_UNSUPPORTED_SHAPE;
+    if (!ok_ptr(w_bf16) || !ok_ptr(codes) || (codes_t != nullptr && !aligned16(codes_t)) || state == nullptr)
+        return SB_INVALID_ARG;
+    if (ws == nullptr || !aligned16(ws)) return SB_INVALID_ARG;
+    if (ws_bytes < switchback_workspace_bytes(SB_OP_QUANTIZE_TENSORWISE, 0, cols, rows))
+        return SB_WORKSPACE_TOO_SMALL;
+    return from_hip(sb::launch_quantize_tensorwise_f8(w_bf16, rows, cols, fmt, codes, codes_t, state,
+                                                      static_cast<unsigned int *>(ws),
+                                                      static_cast<hipStream_t>(stream)));
+}
+
+int switchback_matmul_f8_dequant(const uint8_t *aq, sb_f8_format fmt_a, const float *state_row, const uint8_t *bq,
+                                 sb_f8_format fmt_b, const float *state_tensor, int64_t M, int64_t N, int64_t K,
+                                 void *out, sb_dtype out_dtype, void *stream) {
+    if (M < 0 || N <= 0 || K <= 0 || !ok_f8(fmt_a) || !ok_f8(fmt_b)) return SB_INVALID_ARG;
+    if (out_dtype != SB_BF16 && out_dtype != SB_F32) return SB_INVALID_ARG;
+    if (K % 128 || N % 64 || K > kMaxIntK || N > kMaxIntK || M > (int64_t)1 << 30) return SB_UNSUPPORTED_SHAPE;
+    if ((M + 256) * K >= (int64_t)1 << 32 || (N + 256) * K >= (int64_t)1 << 32) return SB_UNSUPPORTED_SHAPE;
+    if (M * N * 2 >= (int64_t)1 << 32) return SB_UNSUPPORTED_SHAPE;
+    if (M == 0) return SB_OK;
+    if (!ok_ptr(aq) || !ok_ptr(bq) || !ok_ptr(out) || state_row == nullptr || state_tensor == nullptr)
+        return SB_INVALID_ARG;
+    return from_hip(sb::launch_gemm_f8_dequant(aq, fmt_a, state_row, bq, fmt_b, state_tensor, M, N, K, out, out_dtype,
+                                               static_cast<hipStream_t>(stream)));
+}
+
+int switchback_forward_f8(const void *x_bf16, const void *w_bf16, int64_t b, int64_t n, int64_t m, void *y,
+                          sb_dtype y_dtype, const sb_saved *saved, sb_f8_format fmt_x, sb_f8_format fmt_w, void *ws,
+                          size_t ws_bytes, void *stream) {
+    int st = layer_shape_status(b, n, m);
+    if (st != SB_OK) return st;
+    if (n % 128 || m % 128) return SB_UNSUPPORTED_SHAPE;
+    if ((y_dtype != SB_BF16 && y_dtype != SB_F32) || saved == nullptr || !ok_f8(fmt_x) || !ok_f8(fmt_w))
+        return SB_INVALID_ARG;
+    if (!ok_ptr(w_bf16) || !ok_ptr(saved->wq) || !ok_ptr(saved->wq_t) || saved->state_w == nullptr)
+        return SB_INVALID_ARG;
+    if (b > 0 && (!ok_ptr(x_bf16) || !ok_ptr(y) || !ok_ptr(saved->xq) || saved->state_x == nullptr))
+        return SB_INVALID_ARG;
+    if (ws == nullptr || !aligned16(ws)) return SB_INVALID_ARG;
+    if (ws_bytes < switchback_workspace_bytes(SB_OP_FORWARD, b, n, m)) return SB_WORKSPACE_TOO_SMALL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint8_t *xq = reinterpret_cast<uint8_t *>(saved->xq), *wq = reinterpret_cast<uint8_t *>(saved->wq);
+    // The forward pass of Algorithm 1 with float8cast(x / absmax) as the quantizer.
+    hipError_t e = sb::launch_quantize_tensorwise_f8(w_bf16, m, n, fmt_w, wq, reinterpret_cast<uint8_t *>(saved->wq_t),
+                                                     saved->state_w, static_cast<unsigned int *>(ws), s);
+    if (e != hipSuccess) return SB_HIP_ERROR;
+    if (b == 0) return SB_OK;
+    e = sb::launch_quantize_rowwise_f8(x_bf16, b, n, fmt_x, xq, saved->state_x, s);
+    if (e != hipSuccess) return SB_HIP_ERROR;
+    return from_hip(sb::launch_gemm_f8_dequant(xq, fmt_x, saved->state_x, wq, fmt_w, saved->state_w, b, m, n, y,
+                                               y_dtype, s));
+}
+
+int switchback_backward_input_f8(const void *dy_bf16, const sb_saved *saved, int64_t b, int64_t n, int64_t m, void *dx,
+                                 sb_dtype dx_dtype, uint8_t *gq, float *state_g, sb_f8_format fmt_g,
+                                 sb_f8_format fmt_w, void *stream) {
+    int st = layer_shape_status(b, n, m);
+    if (st != SB_OK) return st;
+    if (n % 128 || m % 128) return SB_UNSUPPORTED_SHAPE;
+    if ((dx_dtype != SB_BF16 && dx_dtype != SB_F32) || saved == nullptr || !ok_f8(fmt_g) || !ok_f8(fmt_w))
+        return SB_INVALID_ARG;
+    if (b == 0) return SB_OK;
+    if (!ok_ptr(dy_bf16) || !ok_ptr(dx) || !ok_ptr(gq) || state_g == nullptr || !ok_ptr(saved->wq_t) ||
+        saved->state_w == nullptr)
+        return SB_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = sb::launch_quantize_rowwise_f8(dy_bf16, b, m, fmt_g, gq, state_g, s);
+    if (e != hipSuccess) return SB_HIP_ERROR;
+    return from_hip(sb::launch_gemm_f8_dequant(gq, fmt_g, state_g, reinterpret_cast<const uint8_t *>(saved->wq_t), fmt_w,
+                                               saved->state_w, b, n, m, dx, dx_dtype, s));
 }
 
 int switchback_stable_adamw_step(float *theta, float *v, float *u, const void *grad, sb_dtype grad_dtype,

@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libswitchback.so")
 SB_BF16, SB_F32, SB_I32_RAW = 0, 1, 2
 SB_OP_QUANTIZE_TENSORWISE, SB_OP_FORWARD, SB_OP_BACKWARD_INPUT, SB_OP_BACKWARD_WEIGHT, SB_OP_QUANTIZE_COLWISE = 0, 1, 2, 3, 4
 SB_OP_STABLE_ADAMW = 5
+SB_E4M3, SB_E5M2 = 0, 1
 
 _TORCH_DTYPE = {SB_BF16: torch.bfloat16, SB_F32: torch.float32, SB_I32_RAW: torch.int32}
 _SB_DTYPE = {v: k for k, v in _TORCH_DTYPE.items()}
@@ -57,6 +58,11 @@ def load_library():
     lib.switchback_forward_q.argtypes = [vp, vp, i64, i64, i64, vp, ci, vp, vp, vp, vp, vp]
     lib.switchback_backward_input_q.argtypes = [vp, vp, i64, i64, i64, vp, ci, vp, vp, vp, vp, vp, sz, vp]
     cf = ctypes.c_float
+    lib.switchback_quantize_rowwise_f8.argtypes = [vp, i64, i64, ci, vp, vp, vp]
+    lib.switchback_quantize_tensorwise_f8.argtypes = [vp, i64, i64, ci, vp, vp, vp, vp, sz, vp]
+    lib.switchback_matmul_f8_dequant.argtypes = [vp, ci, vp, vp, ci, vp, i64, i64, i64, vp, ci, vp]
+    lib.switchback_forward_f8.argtypes = [vp, vp, i64, i64, i64, vp, ci, ctypes.POINTER(SbSaved), ci, ci, vp, sz, vp]
+    lib.switchback_backward_input_f8.argtypes = [vp, ctypes.POINTER(SbSaved), i64, i64, i64, vp, ci, vp, vp, ci, ci, vp]
     lib.switchback_stable_adamw_step.argtypes = [vp, vp, vp, vp, ci, i64, cf, cf, cf, cf, cf, i64, vp, vp, sz, vp]
     lib.switchback_workspace_bytes.argtypes = [ci, i64, i64, i64]
     lib.switchback_workspace_bytes.restype = sz
@@ -66,7 +72,9 @@ def load_library():
                  "switchback_forward", "switchback_backward_input", "switchback_backward_weight",
                  "switchback_dequantize_rowwise", "switchback_backward_weight_m",
                  "switchback_quantize_colwise_transpose", "switchback_matmul_int8_dequant_rc",
-                 "switchback_forward_q", "switchback_backward_input_q", "switchback_stable_adamw_step"):
+                 "switchback_forward_q", "switchback_backward_input_q", "switchback_stable_adamw_step",
+                 "switchback_quantize_rowwise_f8", "switchback_quantize_tensorwise_f8", "switchback_matmul_f8_dequant",
+                 "switchback_forward_f8", "switchback_backward_input_f8"):
         getattr(lib, name).restype = ci
     _lib = lib
     return lib
@@ -316,3 +324,68 @@ def stable_adamw_step(theta, v, u, grad, alpha, beta1, beta2, eps, lam, t, rms_o
                                             _SB_DTYPE[grad.dtype], count, alpha, beta1, beta2, eps, lam, t,
                                             _ptr(rms_out), _ptr(ws), ws.numel(), _stream()))
     return rms_out
+
+
+# ---- float8 SwitchBack: the same layer with float8cast(x / absmax) as the quantizer; codes are uint8 tensors ------
+
+def quantize_rowwise_f8(x, fmt, codes=None, state=None):
+    lib = load_library()
+    xp = _dev(x, torch.bfloat16, 2)
+    rows, cols = x.shape
+    codes = torch.empty((rows, cols), dtype=torch.uint8, device=x.device) if codes is None else codes
+    state = torch.empty(rows, dtype=torch.float32, device=x.device) if state is None else state
+    _check(lib.switchback_quantize_rowwise_f8(xp, rows, cols, fmt, _ptr(codes), _ptr(state), _stream()))
+    return codes, state
+
+
+def quantize_tensorwise_f8(w, fmt, codes=None, codes_t=None, state=None, ws=None):
+    lib = load_library()
+    wp = _dev(w, torch.bfloat16, 2)
+    rows, cols = w.shape
+    codes = torch.empty((rows, cols), dtype=torch.uint8, device=w.device) if codes is None else codes
+    codes_t = torch.empty((cols, rows), dtype=torch.uint8, device=w.device) if codes_t is None else codes_t
+    state = torch.empty(1, dtype=torch.float32, device=w.device) if state is None else state
+    ws = _workspace(SB_OP_QUANTIZE_TENSORWISE, 0, cols, rows, w.device) if ws is None else ws
+    _check(lib.switchback_quantize_tensorwise_f8(wp, rows, cols, fmt, _ptr(codes), _ptr(codes_t), _ptr(state),
+                                                 _ptr(ws), ws.numel(), _stream()))
+    return codes, codes_t, state
+
+
+def matmul_f8_dequant(aq, fmt_a, state_row, bq, fmt_b, state_tensor, out=None, out_dtype=torch.bfloat16):
+    lib = load_library()
+    M, K = aq.shape
+    N = bq.shape[0]
+    if bq.shape[1] != K:
+        raise SwitchBackError("aq [M,K] and bq [N,K] disagree on K")
+    out = torch.empty((M, N), dtype=out_dtype, device=aq.device) if out is None else out
+    _check(lib.switchback_matmul_f8_dequant(_dev(aq, torch.uint8, 2), fmt_a, _ptr(state_row), _dev(bq, torch.uint8, 2),
+                                            fmt_b, _ptr(state_tensor), M, N, K, _dev(out, out.dtype, 2),
+                                            _SB_DTYPE[out.dtype], _stream()))
+    return out
+
+
+def forward_f8(x, w, bufs=None, y=None, y_dtype=torch.bfloat16, fmt_x=SB_E4M3, fmt_w=SB_E4M3):
+    """float8 SwitchBack forward.  Returns (y [b,m], bufs); bufs (a LayerBuffers) then holds float8 bytes."""
+    lib = load_library()
+    b, n = x.shape
+    m = w.shape[0]
+    if w.shape[1] != n:
+        raise SwitchBackError("x [b,n] and w [m,n] disagree on n")
+    bufs = LayerBuffers(b, n, m, x.device) if bufs is None else bufs
+    y = torch.empty((b, m), dtype=y_dtype, device=x.device) if y is None else y
+    _check(lib.switchback_forward_f8(_dev(x, torch.bfloat16, 2), _dev(w, torch.bfloat16, 2), b, n, m,
+                                     _dev(y, y_dtype, 2), _SB_DTYPE[y_dtype], ctypes.byref(bufs.saved), fmt_x, fmt_w,
+                                     _ptr(bufs.ws_fwd), bufs.ws_fwd.numel(), _stream()))
+    return y, bufs
+
+
+def backward_input_f8(dy, bufs, dx=None, dx_dtype=torch.bfloat16, fmt_g=SB_E5M2, fmt_w=SB_E4M3):
+    """float8 SwitchBack input gradient.  Returns dx [b,n]; fills bufs.gq (float8 bytes) and bufs.state_g."""
+    lib = load_library()
+    b, m = dy.shape
+    n = bufs.n
+    dx = torch.empty((b, n), dtype=dx_dtype, device=dy.device) if dx is None else dx
+    _check(lib.switchback_backward_input_f8(_dev(dy, torch.bfloat16, 2), ctypes.byref(bufs.saved), b, n, m,
+                                            _dev(dx, dx_dtype, 2), _SB_DTYPE[dx_dtype], _ptr(bufs.gq),
+                                            _ptr(bufs.state_g), fmt_g, fmt_w, _stream()))
+    return dx

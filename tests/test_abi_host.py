@@ -98,6 +98,20 @@ def test_bad_arguments_are_rejected_before_launch(lib):
     assert lib.switchback_backward_weight(fake, fake, 8, 64, 64, fake, 2, fake, 1 << 30, null) == INVALID
     assert lib.switchback_backward_weight(fake, fake, 32896, 1280, 1280, fake, 0, fake, 64, null) == WS
     assert lib.switchback_backward_weight(fake, fake, 8, 64, 64, null, 0, fake, 1 << 30, null) == INVALID
+    assert lib.switchback_quantize_rowwise_f8(fake, 4, 64, 2, fake, fake, null) == INVALID       # unknown format
+    assert lib.switchback_quantize_rowwise_f8(fake, 4, 60, 0, fake, fake, null) == SHAPE
+    assert lib.switchback_quantize_rowwise_f8(null, 0, 64, 1, null, null, null) == 0
+    assert lib.switchback_quantize_tensorwise_f8(fake, 64, 64, 0, fake, fake, fake, fake, 16, null) == WS
+    assert lib.switchback_quantize_tensorwise_f8(fake, 64, 64, 5, fake, fake, fake, fake, 1 << 20, null) == INVALID
+    assert lib.switchback_matmul_f8_dequant(fake, 0, fake, fake, 0, fake, 8, 64, 64, fake, 0, null) == SHAPE   # K % 128
+    assert lib.switchback_matmul_f8_dequant(fake, 0, fake, fake, 0, fake, 8, 64, 128, fake, 2, null) == INVALID
+    assert lib.switchback_matmul_f8_dequant(fake, 0, null, fake, 0, fake, 8, 64, 128, fake, 0, null) == INVALID
+    assert lib.switchback_forward_f8(fake, fake, 8, 64, 128, fake, 0, sp, 0, 0, fake, 1 << 20, null) == SHAPE
+    assert lib.switchback_forward_f8(fake, fake, 8, 128, 128, fake, 0, sp, 0, 3, fake, 1 << 20, null) == INVALID
+    assert lib.switchback_forward_f8(fake, fake, 8, 128, 128, fake, 0, sp, 0, 0, fake, 8, null) == WS
+    assert lib.switchback_backward_input_f8(fake, sp, 8, 128, 192, fake, 0, fake, fake, 1, 0, null) == SHAPE
+    assert lib.switchback_backward_input_f8(null, sp, 8, 128, 128, fake, 0, fake, fake, 1, 0, null) == INVALID
+    assert lib.switchback_backward_input_f8(null, sp, 0, 128, 128, null, 0, null, null, 1, 0, null) == 0
     adam = lib.switchback_stable_adamw_step
     good = (1e-3, 0.9, 0.98, 1e-6, 0.2)
     assert adam(fake, fake, fake, fake, 0, 100, *good, 0, null, fake, 1 << 20, null) == INVALID    # t starts at 1

@@ -503,3 +503,168 @@ def test_stable_adamw_is_deterministic_and_leaves_grad_alone():
         outs.append((host(th_d), host(v_d), host(u_d), host(rms)))
     for a, b in zip(*outs):
         np.testing.assert_array_equal(a.view(np.uint32), b.view(np.uint32))
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# float8 SwitchBack (float8cast(x / absmax(x)) as the quantizer, real 8-bit float matrix instructions).  Codes and
+# states bit-exact.  The product is compared with the oracle's exact sum under the error bound of the matrix
+# instruction's arithmetic, which single-instruction probes with crafted operands show to be: the 64 products of one
+# instruction are summed in groups of 8 consecutive k; inside a group every product is aligned to the largest one and
+# TRUNCATED below 2^-13 of that product's power of two (a 14-bit window); group sums and the accumulator are then added
+# at binary32 precision or better.  Hence per group an error below 7 * 2^-13 * max|a_k b_k|, in total below
+# 7 * 2^-13 * sum_k |a_k b_k|, plus 2^-23 of that sum for each of the K/64 + 8 binary32 additions a result passes
+# through.  (The paper's own float8 runs do this arithmetic in 16 bit, i.e. with 8 to 11 significant bits.)
+# ---------------------------------------------------------------------------------------------------------------
+
+def u8_dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def f8_product_tolerance(abs_acc, r, K):
+    return (7 * 2.0 ** -13 + (K / 64 + 8) * 2.0 ** -23) * abs_acc * np.abs(r.astype(np.float64))[:, None]
+
+
+def assert_f8_outputs(got32, got_bf16_bits, acc, abs_acc, state_row, state_w, K, oracle):
+    r = (state_row * np.float32(state_w)).astype(np.float32)
+    y32, y64 = oracle.dequantize_f8(acc, state_row, state_w, want_f64=True)
+    tol = f8_product_tolerance(abs_acc, r, K) + ulp(y32)
+    if got32 is not None:
+        err = np.abs(got32.astype(np.float64) - y64)
+        assert (err <= tol).all(), "float8 product off by %.3g, %.2f of the tolerance" % (err.max(), (err / tol).max())
+    if got_bf16_bits is not None:
+        got = I.bf16_bits_to_f32(got_bf16_bits).astype(np.float64)
+        half_bf16_ulp = np.abs(y64) * 2.0 ** -8 + 1e-45
+        assert (np.abs(got - y64) <= tol + half_bf16_ulp).all()
+
+
+@pytest.mark.parametrize("fmt", [0, 1])
+@pytest.mark.parametrize("rows,cols", [(512, 256), (1, 8), (5, 520), (257, 1280), (9, 2056), (33, 5120), (5, 12296),
+                                       (3, 16392), (2, 65536)])
+def test_float8_quantize_rowwise(oracle, rows, cols, fmt):
+    x = rand_bf16(np.random.default_rng(rows * 17 + cols + fmt), (rows, cols), 2.0)
+    if rows >= 8:
+        I.plant_edge_rows(x)
+    codes, state = sb.quantize_rowwise_f8(to_dev(x), fmt)
+    torch.cuda.synchronize()
+    co, so = oracle.quantize_rowwise_f8(x, fmt)
+    np.testing.assert_array_equal(host(state).view(np.uint32), so.view(np.uint32))
+    np.testing.assert_array_equal(host(codes), co)
+
+
+@pytest.mark.parametrize("fmt", [0, 1])
+@pytest.mark.parametrize("rows,cols", [(1024, 256), (16, 16), (272, 144), (1280, 5120)])
+def test_float8_quantize_tensorwise(oracle, rows, cols, fmt):
+    w = rand_bf16(np.random.default_rng(rows + cols + fmt), (rows, cols), cols ** -0.5)
+    w[rows // 2, cols // 3] = np.uint16(0xC000)                   # -2.0: the absmax, negative
+    codes, codes_t, state = sb.quantize_tensorwise_f8(to_dev(w), fmt)
+    torch.cuda.synchronize()
+    co, cto, so = oracle.quantize_tensorwise_f8(w, fmt)
+    assert host(state).view(np.uint32)[0] == np.float32(so).view(np.uint32)
+    np.testing.assert_array_equal(host(codes), co)
+    np.testing.assert_array_equal(host(codes_t), cto)
+
+
+def layer_like_codes(rng, shape, fmt):
+    """Random codes with |value| <= 1 (what the quantizers emit), all exponents of the format's [0, 1] range."""
+    one = 0x38 if fmt == 0 else 0x3C
+    mag = rng.integers(0, one + 1, shape).astype(np.uint8)
+    return mag | (rng.integers(0, 2, shape).astype(np.uint8) << 7)
+
+
+@pytest.mark.parametrize("fa,fb", [(0, 0), (1, 0), (0, 1), (1, 1)])
+@pytest.mark.parametrize("M,N,K", [(300, 320, 256), (512, 256, 1024), (1, 64, 128), (257, 576, 384)])
+def test_float8_product(oracle, M, N, K, fa, fb):
+    rng = np.random.default_rng(M + N + K + 2 * fa + fb)
+    a, b = layer_like_codes(rng, (M, K), fa), layer_like_codes(rng, (N, K), fb)
+    sr = rng.uniform(0.5, 4.0, M).astype(np.float32)
+    sw = np.float32(0.37)
+    acc, abs_acc = oracle.matmul_f8(a, fa, b, fb, want_abs=True)
+    sw_d = torch.tensor([sw], dtype=torch.float32, device=DEV)
+    o32 = sb.matmul_f8_dequant(u8_dev(a), fa, u8_dev(sr), u8_dev(b), fb, sw_d, out_dtype=torch.float32)
+    obf = sb.matmul_f8_dequant(u8_dev(a), fa, u8_dev(sr), u8_dev(b), fb, sw_d, out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    assert_f8_outputs(host(o32), bits_of(obf), acc, abs_acc, sr, sw, K, oracle)
+
+
+@pytest.mark.parametrize("fa,fb", [(0, 0), (1, 0)])
+def test_float8_product_is_exact_when_binary32_can_hold_every_partial_sum(oracle, fa, fb):
+    """Codes of 0, +-0.25, +-0.5, +-1: every product and partial sum is a small multiple of 1/16, exact in binary32
+    in any order, so the result must equal the oracle's bit for bit -- each operand byte reaches the right k."""
+    rng = np.random.default_rng(5 + fa)
+    M, N, K = 333, 192, 640
+    pick = {0: np.array([0x00, 0x28, 0x30, 0x38], np.uint8), 1: np.array([0x00, 0x34, 0x38, 0x3C], np.uint8)}
+    a = pick[fa][rng.integers(0, 4, (M, K))] | (rng.integers(0, 2, (M, K)).astype(np.uint8) << 7)
+    b = pick[fb][rng.integers(0, 4, (N, K))] | (rng.integers(0, 2, (N, K)).astype(np.uint8) << 7)
+    a[:, ::7] = 0                                                   # break any symmetry between k positions
+    sr = np.ones(M, np.float32)
+    one = torch.ones(1, dtype=torch.float32, device=DEV)
+    o32 = sb.matmul_f8_dequant(u8_dev(a), fa, u8_dev(sr), u8_dev(b), fb, one, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    acc = oracle.matmul_f8(a, fa, b, fb)
+    assert np.abs(acc).max() > 10
+    np.testing.assert_array_equal(host(o32).astype(np.float64), acc)
+
+
+def check_layer_f8(oracle, d, rows=None):
+    x, w, dy = to_dev(d["x"]), to_dev(d["w"]), to_dev(d["dy"])
+    b, n = d["x"].shape
+    m = d["w"].shape[0]
+    bufs = sb.LayerBuffers(b, n, m, DEV)
+    y32, _ = sb.forward_f8(x, w, bufs=bufs, y_dtype=torch.float32)
+    ybf, _ = sb.forward_f8(x, w, bufs=bufs, y_dtype=torch.bfloat16)
+    dx32 = sb.backward_input_f8(dy, bufs, dx_dtype=torch.float32)
+    dxbf = sb.backward_input_f8(dy, bufs, dx_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    xq, sx = oracle.quantize_rowwise_f8(d["x"], oracle.E4M3)
+    wq, wq_t, sw = oracle.quantize_tensorwise_f8(d["w"], oracle.E4M3)
+    gq, sg = oracle.quantize_rowwise_f8(d["dy"], oracle.E5M2)
+    as_u8 = lambda t: host(t).view(np.uint8)
+    np.testing.assert_array_equal(as_u8(bufs.xq), xq)
+    np.testing.assert_array_equal(host(bufs.state_x).view(np.uint32), sx.view(np.uint32))
+    np.testing.assert_array_equal(as_u8(bufs.wq), wq)
+    np.testing.assert_array_equal(as_u8(bufs.wq_t), wq_t)
+    assert host(bufs.state_w).view(np.uint32)[0] == np.float32(sw).view(np.uint32)
+    np.testing.assert_array_equal(as_u8(bufs.gq), gq)
+    np.testing.assert_array_equal(host(bufs.state_g).view(np.uint32), sg.view(np.uint32))
+    rows = np.arange(b) if rows is None else rows
+    idx = torch.from_numpy(rows).to(DEV)
+    acc, abs_acc = oracle.matmul_f8(xq[rows], oracle.E4M3, wq, oracle.E4M3, want_abs=True)
+    assert_f8_outputs(host(y32[idx]), bits_of(ybf[idx]), acc, abs_acc, sx[rows], sw, n, oracle)
+    acc, abs_acc = oracle.matmul_f8(gq[rows], oracle.E5M2, wq_t, oracle.E4M3, want_abs=True)
+    assert_f8_outputs(host(dx32[idx]), bits_of(dxbf[idx]), acc, abs_acc, sg[rows], sw, m, oracle)
+    return host(y32), host(dx32)
+
+
+def test_float8_layer_tiny_with_edge_rows(oracle):
+    d = I.make_layer_inputs("tiny")
+    I.plant_edge_rows(d["x"])
+    I.plant_edge_rows(d["dy"])
+    y, dx = check_layer_f8(oracle, d)
+    assert not y[0].any()                  # zero row -> zero output (1/1e-38 is finite: the tiny row is a live row here)
+
+
+@pytest.mark.parametrize("b,n,m", [(1, 128, 128), (33, 256, 384), (300, 128, 640), (1000, 384, 256)])
+def test_float8_layer_ragged_shapes(oracle, b, n, m):
+    rng = np.random.default_rng(b + n + m)
+    d = dict(x=rand_bf16(rng, (b, n)), w=rand_bf16(rng, (m, n), n ** -0.5), dy=rand_bf16(rng, (b, m), 0.1))
+    check_layer_f8(oracle, d)
+
+
+@pytest.mark.parametrize("config,layer", [("vit_h14", 2), ("vit_h14", 3), ("outlier", 0)])
+def test_float8_layer_full_size_sampled(oracle, config, layer):
+    L = I.CONFIGS[config].layers[layer]
+    d = I.make_layer_inputs(config, layer)
+    rng = np.random.default_rng(29)
+    rows = np.unique(np.concatenate([[0, 255, 256, L.b - 257, L.b - 1], rng.integers(0, L.b, 16)]))
+    check_layer_f8(oracle, d, rows)
+
+
+def test_float8_layer_is_deterministic_and_rejects_unsupported_widths():
+    d = I.make_layer_inputs("tiny")
+    x, w = to_dev(d["x"]), to_dev(d["w"])
+    a, _ = sb.forward_f8(x, w)
+    b, _ = sb.forward_f8(x, w)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(bits_of(a), bits_of(b))
+    with pytest.raises(sb.SwitchBackError):
+        sb.forward_f8(x[:, :192].contiguous(), w[:, :192].contiguous())     # n % 128 != 0
