@@ -123,6 +123,14 @@ def main():
             sb.backward_input_q(t["dy"], t["w"], q_bufs[i], dx=t["dx"])
             sb.backward_weight(t["dy"], t["x"], t["bufs"], dw=t["dw"])
 
+    def switchback_f8_step():
+        # The float8 variant: float8cast(x / absmax) quantizers (E4M3 for X and W, E5M2 for dY), float8 MFMA products.
+        # Shares the layer buffers with the int8 path (same sizes), so it runs after the int8 measurements.
+        for t in layers:
+            sb.forward_f8(t["x"], t["w"], bufs=t["bufs"], y=t["y"])
+            sb.backward_input_f8(t["dy"], t["bufs"], dx=t["dx"])
+            sb.backward_weight(t["dy"], t["x"], t["bufs"], dw=t["dw"])
+
     def bf16_step():
         for t in layers:
             torch.matmul(t["x"], t["w"].t(), out=t["y"])
@@ -149,6 +157,9 @@ def main():
     variant_m_ms, _ = timed(switchback_m_step, max(3, args.steps // 2), 2)
     variant_q_ms, _ = timed(switchback_q_step, max(3, args.steps // 2), 2)
     q_bufs.clear()
+    variant_f8_ms = None
+    if all(L.n % 128 == 0 and L.m % 128 == 0 for L in cfg.layers):
+        variant_f8_ms, _ = timed(switchback_f8_step, max(3, args.steps // 2), 2)
 
     # ---- per-kernel times: the same kernels on the same shapes, one event pair around each launch group ------
     ops = {}  # name -> [total ms over reps, algorithmic work, unit kind]
@@ -191,6 +202,19 @@ def main():
                 2.0 * b * n * m, "int8", reps)
         time_op("gemm_bf16_weight_grad", lambda: sb.backward_weight(t["dy"], t["x"], bufs, dw=t["dw"]),
                 2.0 * b * n * m, "bf16", reps)
+        if L.n % 128 == 0 and L.m % 128 == 0:
+            # float8 variant: quantize into the same buffers (afterwards they hold float8 bytes), then the two products
+            sb.forward_f8(t["x"], t["w"], bufs=bufs, y=t["y"])
+            sb.backward_input_f8(t["dy"], bufs, dx=t["dx"])
+            u8 = lambda q: q.view(torch.uint8)
+            time_op("gemm_f8_dequant (float8 variant)",
+                    lambda: sb.matmul_f8_dequant(u8(bufs.xq), sb.SB_E4M3, bufs.state_x, u8(bufs.wq), sb.SB_E4M3,
+                                                 bufs.state_w, out=t["y"]),
+                    2.0 * b * n * m, "f8", reps)
+            time_op("gemm_f8_dequant (float8 variant)",
+                    lambda: sb.matmul_f8_dequant(u8(bufs.gq), sb.SB_E5M2, bufs.state_g, u8(bufs.wq_t), sb.SB_E4M3,
+                                                 bufs.state_w, out=t["dx"]),
+                    2.0 * b * n * m, "f8", reps)
         # The optimizer step that consumes dW (binary32 master weights and moments, bf16 gradient): 34 bytes per
         # parameter (g 2, v and u read + written 16, theta/v/u read 12, theta written 4).  Not part of the step.
         opt = [torch.zeros(m * n, dtype=torch.float32, device=dev) for _ in range(3)]
@@ -208,7 +232,7 @@ def main():
             ach, peak, unit, bound = work / ms / 1e6, PEAK["hbm_GBps"], "GB/s", "hbm"
         else:
             ach, unit, bound = work / ms / 1e9, "TFLOP/s", "mfma"
-            peak = PEAK["int8_TOPs"] if kind == "int8" else PEAK["bf16_TFLOPs"]
+            peak = PEAK["bf16_TFLOPs"] if kind == "bf16" else PEAK["int8_TOPs"]  # int8 and float8: 5.0 P(FL)OP/s dense
         kernels[name] = {"ms_per_step": round(ms, 4), "bound": bound, "achieved": round(ach, 1), "peak": peak,
                          "unit": unit, "frac": round(ach / peak, 4)}
     in_step = [k for k in kernels if "(" not in k]  # names with a parenthesis are measured beside the step
@@ -271,6 +295,7 @@ def main():
         "ms_per_step_w_requantized_in_backward": round(requant_ms, 4),
         "ms_per_step_switchback_m": round(variant_m_ms, 4),
         "ms_per_step_switchback_q": round(variant_q_ms, 4),
+        "ms_per_step_switchback_float8": None if variant_f8_ms is None else round(variant_f8_ms, 4),
         "roofline": roofline,
         "kernels": kernels,
         "sum_of_kernel_ms": round(op_sum, 4),
