@@ -226,6 +226,17 @@ def main():
                 34.0 * m * n, "bytes", reps)
         del opt
 
+    # The same optimizer step for the four weights of the block in one launch pair.
+    opt_all = [tuple(torch.zeros(t["L"].m * t["L"].n, dtype=torch.float32, device=dev) for _ in range(3)) + (t["dw"],)
+               for t in layers]
+    for o in opt_all:
+        o[2].fill_(1e-6)
+    plan = sb.AdamwPlan(opt_all)
+    time_op("stable_adamw_step_multi (optimizer, the block's 4 weights in one launch pair)",
+            lambda: sb.stable_adamw_step_multi(plan, 1e-3, 0.9, 0.98, 1e-6, 0.2, 10),
+            34.0 * sum(t["L"].m * t["L"].n for t in layers), "bytes", reps)
+    del plan, opt_all
+
     kernels = {}
     for name, (ms, work, kind) in ops.items():
         if kind == "bytes":

@@ -201,6 +201,31 @@ int switchback_stable_adamw_step(float *theta, float *v, float *u, const void *g
                                  int64_t count, float alpha, float beta1, float beta2, float eps, float lambda,
                                  int64_t t, float *rms_out, void *ws, size_t ws_bytes, void *stream);
 
+/* The same step for many tensors in two launches (a model has hundreds of parameter tensors, most of them small; one
+ * launch pair per tensor would be bound by launch overhead).  Each tensor is clipped by its own RMS_t exactly as in
+ * switchback_stable_adamw_step, and gets the same number of workgroups as there, so the results are bit-identical
+ * to per-tensor calls.
+ *   switchback_stable_adamw_plan (host only, touches no GPU): fills first_block / num_blocks of a HOST table of n
+ *     entries whose theta, v, u, grad, count are set, and returns the total number of workgroups (0 if n == 0,
+ *     negative status code on a bad entry).  The caller then copies the table to the device once; it stays valid
+ *     while the pointers do.
+ *   switchback_stable_adamw_step_multi: table_dev is that device copy (16-byte aligned), total_blocks the plan's
+ *     return value; all gradients share grad_dtype; rms_out: optional device array [n]; ws: at least
+ *     8 * total_blocks bytes (partial sums).  Hyper-parameters as in the single-tensor call. */
+typedef struct sb_adamw_tensor {
+    float *theta;      /* [count] f32, updated in place        */
+    float *v;          /* [count] f32 first moment             */
+    float *u;          /* [count] f32 second moment            */
+    const void *grad;  /* [count] SB_BF16 or SB_F32            */
+    int64_t count;     /* > 0                                  */
+    int32_t first_block;
+    int32_t num_blocks;
+} sb_adamw_tensor;
+int64_t switchback_stable_adamw_plan(sb_adamw_tensor *table_host, int n);
+int switchback_stable_adamw_step_multi(const sb_adamw_tensor *table_dev, int n, int64_t total_blocks,
+                                       sb_dtype grad_dtype, float alpha, float beta1, float beta2, float eps,
+                                       float lambda, int64_t t, float *rms_out, void *ws, size_t ws_bytes, void *stream);
+
 /* Bytes of device workspace `op` needs for a layer of this shape (0 if none).  Shape arguments an op does not
  * use are ignored (for SB_OP_QUANTIZE_TENSORWISE pass rows as m and cols as n). */
 size_t switchback_workspace_bytes(int op, int64_t b, int64_t n, int64_t m);

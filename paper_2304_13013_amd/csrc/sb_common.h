@@ -62,6 +62,11 @@ hipError_t launch_stable_adamw_step(float *theta, float *v, float *u, const void
                                     float alpha, float b1_hat, float b2_hat, float omb1, float omb2, float eps,
                                     float lambda, float *rms_out, void *ws, hipStream_t stream);
 
+int stable_adamw_blocks(int64_t count);  // workgroups a tensor of this many elements gets (single and batched launch)
+hipError_t launch_stable_adamw_step_multi(const sb_adamw_tensor *table, int n, int total_blocks, bool grad_bf16,
+                                          float alpha, float b1_hat, float b2_hat, float omb1, float omb2, float eps,
+                                          float lambda, float *rms_out, void *ws, hipStream_t stream);
+
 constexpr int kTensorwisePartials = 1024;  // upper bound on blocks of the tensor-wise absmax pass
 constexpr int kAdamwPartials = 2048;  // upper bound on the workgroups of a StableAdamW step
 constexpr int kColwiseRuns = 64;  // upper bound on the row runs of the column-wise absmax pass

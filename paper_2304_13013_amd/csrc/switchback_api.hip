@@ -24,6 +24,12 @@ int layer_shape_status(int64_t b, int64_t n, int64_t m) {
 
 int from_hip(hipError_t e) { return e == hipSuccess ? SB_OK : SB_HIP_ERROR; }
 
+// Corrected decay rate of StableAdamW, in binary64: beta (1 - beta^(t-1)) / (1 - beta^t); 0 at t = 1.
+double corrected_decay(double beta, int64_t step) {
+    if (beta == 0.0) return 0.0;
+    return beta * (1.0 - std::pow(beta, (double)(step - 1))) / (1.0 - std::pow(beta, (double)step));
+}
+
 }  // namespace
 
 extern "C" {
@@ -310,15 +316,41 @@ int switchback_stable_adamw_step(float *theta, float *v, float *u, const void *g
     if (!ok_ptr(theta) || !ok_ptr(v) || !ok_ptr(u) || !ok_ptr(grad) || ws == nullptr || !aligned16(ws))
         return SB_INVALID_ARG;
     if (ws_bytes < sb::stable_adamw_workspace_bytes()) return SB_WORKSPACE_TOO_SMALL;
-    // Corrected decay rates of the algorithm, in binary64: beta (1 - beta^(t-1)) / (1 - beta^t); 0 at t = 1.
-    auto corrected = [](double beta, int64_t step) {
-        if (beta == 0.0) return 0.0;
-        return beta * (1.0 - std::pow(beta, (double)(step - 1))) / (1.0 - std::pow(beta, (double)step));
-    };
-    const double b1 = corrected((double)beta1, t), b2 = corrected((double)beta2, t);
+    const double b1 = corrected_decay((double)beta1, t), b2 = corrected_decay((double)beta2, t);
     return from_hip(sb::launch_stable_adamw_step(theta, v, u, grad, grad_dtype == SB_BF16, count, alpha, (float)b1,
                                                  (float)b2, (float)(1.0 - b1), (float)(1.0 - b2), eps, lambda, rms_out,
                                                  ws, static_cast<hipStream_t>(stream)));
+}
+
+int64_t switchback_stable_adamw_plan(sb_adamw_tensor *table_host, int n) {
+    if (n < 0 || (n > 0 && table_host == nullptr)) return -SB_INVALID_ARG;
+    int64_t total = 0;
+    for (int i = 0; i < n; ++i) {
+        sb_adamw_tensor &t = table_host[i];
+        if (t.count <= 0 || !ok_ptr(t.theta) || !ok_ptr(t.v) || !ok_ptr(t.u) || !ok_ptr(t.grad)) return -SB_INVALID_ARG;
+        t.first_block = (int32_t)total;
+        t.num_blocks = sb::stable_adamw_blocks(t.count);
+        total += t.num_blocks;
+        if (total > (int64_t)1 << 30) return -SB_UNSUPPORTED_SHAPE;
+    }
+    return total;
+}
+
+int switchback_stable_adamw_step_multi(const sb_adamw_tensor *table_dev, int n, int64_t total_blocks,
+                                       sb_dtype grad_dtype, float alpha, float beta1, float beta2, float eps,
+                                       float lambda, int64_t t, float *rms_out, void *ws, size_t ws_bytes, void *stream) {
+    if (n < 0 || total_blocks < 0 || t < 1) return SB_INVALID_ARG;
+    if (grad_dtype != SB_BF16 && grad_dtype != SB_F32) return SB_INVALID_ARG;
+    if (!(beta1 >= 0.0f && beta1 < 1.0f) || !(beta2 >= 0.0f && beta2 < 1.0f) || !(eps > 0.0f)) return SB_INVALID_ARG;
+    if (!std::isfinite(alpha) || !std::isfinite(lambda)) return SB_INVALID_ARG;
+    if (n == 0) return total_blocks == 0 ? SB_OK : SB_INVALID_ARG;
+    if (total_blocks < n || total_blocks > (int64_t)1 << 30) return SB_INVALID_ARG;  // every tensor has a workgroup
+    if (!ok_ptr(table_dev) || ws == nullptr || !aligned16(ws)) return SB_INVALID_ARG;
+    if (ws_bytes < (size_t)total_blocks * sizeof(double)) return SB_WORKSPACE_TOO_SMALL;
+    const double b1 = corrected_decay((double)beta1, t), b2 = corrected_decay((double)beta2, t);
+    return from_hip(sb::launch_stable_adamw_step_multi(table_dev, n, (int)total_blocks, grad_dtype == SB_BF16, alpha,
+                                                       (float)b1, (float)b2, (float)(1.0 - b1), (float)(1.0 - b2), eps,
+                                                       lambda, rms_out, ws, static_cast<hipStream_t>(stream)));
 }
 
 size_t switchback_workspace_bytes(int op, int64_t b, int64_t n, int64_t m) {

@@ -28,6 +28,11 @@ class SbSaved(ctypes.Structure):
                 ("wq_t", ctypes.c_void_p), ("state_w", ctypes.c_void_p)]
 
 
+class SbAdamwTensor(ctypes.Structure):
+    _fields_ = [("theta", ctypes.c_void_p), ("v", ctypes.c_void_p), ("u", ctypes.c_void_p), ("grad", ctypes.c_void_p),
+                ("count", ctypes.c_int64), ("first_block", ctypes.c_int32), ("num_blocks", ctypes.c_int32)]
+
+
 class SwitchBackError(RuntimeError):
     pass
 
@@ -64,6 +69,10 @@ def load_library():
     lib.switchback_forward_f8.argtypes = [vp, vp, i64, i64, i64, vp, ci, ctypes.POINTER(SbSaved), ci, ci, vp, sz, vp]
     lib.switchback_backward_input_f8.argtypes = [vp, ctypes.POINTER(SbSaved), i64, i64, i64, vp, ci, vp, vp, ci, ci, vp]
     lib.switchback_stable_adamw_step.argtypes = [vp, vp, vp, vp, ci, i64, cf, cf, cf, cf, cf, i64, vp, vp, sz, vp]
+    lib.switchback_stable_adamw_plan.argtypes = [ctypes.POINTER(SbAdamwTensor), ci]
+    lib.switchback_stable_adamw_plan.restype = i64
+    lib.switchback_stable_adamw_step_multi.argtypes = [vp, ci, i64, ci, cf, cf, cf, cf, cf, i64, vp, vp, sz, vp]
+    lib.switchback_stable_adamw_step_multi.restype = ci
     lib.switchback_workspace_bytes.argtypes = [ci, i64, i64, i64]
     lib.switchback_workspace_bytes.restype = sz
     lib.switchback_status_string.argtypes = [ci]
@@ -389,3 +398,44 @@ def backward_input_f8(dy, bufs, dx=None, dx_dtype=torch.bfloat16, fmt_g=SB_E5M2,
                                             _dev(dx, dx_dtype, 2), _SB_DTYPE[dx_dtype], _ptr(bufs.gq),
                                             _ptr(bufs.state_g), fmt_g, fmt_w, _stream()))
     return dx
+
+
+class AdamwPlan:
+    """The device table of a batched StableAdamW step over a fixed list of (theta, v, u, grad) tensors: built once,
+    valid while the tensors keep their storage."""
+
+    def __init__(self, tensors):
+        lib = load_library()
+        self.tensors = [tuple(t) for t in tensors]           # keeps the storage alive
+        n = len(self.tensors)
+        if n == 0:
+            raise SwitchBackError("an optimizer plan needs at least one tensor")
+        dtypes = {g.dtype for (_, _, _, g) in self.tensors}
+        if len(dtypes) != 1 or next(iter(dtypes)) not in (torch.bfloat16, torch.float32):
+            raise SwitchBackError("all gradients of a plan must share one dtype, bf16 or f32")
+        self.grad_dtype = next(iter(dtypes))
+        table = (SbAdamwTensor * n)()
+        for i, (theta, v, u, g) in enumerate(self.tensors):
+            for x in (theta, v, u):
+                _dev(x, torch.float32)
+            if not (theta.numel() == v.numel() == u.numel() == g.numel()) or not g.is_cuda or not g.is_contiguous():
+                raise SwitchBackError("tensor %d: theta, v, u and grad must be contiguous GPU tensors of one size" % i)
+            table[i] = SbAdamwTensor(theta.data_ptr(), v.data_ptr(), u.data_ptr(), g.data_ptr(), theta.numel(), 0, 0)
+        total = lib.switchback_stable_adamw_plan(table, n)
+        if total < 0:
+            _check(-total)
+        self.n, self.total_blocks = n, int(total)
+        device = self.tensors[0][0].device
+        raw = torch.frombuffer(bytearray(bytes(table)), dtype=torch.uint8)
+        self.table = raw.to(device)
+        self.ws = torch.empty(max(8 * self.total_blocks, 16), dtype=torch.uint8, device=device)
+        self.rms = torch.empty(n, dtype=torch.float32, device=device)
+
+
+def stable_adamw_step_multi(plan, alpha, beta1, beta2, eps, lam, t):
+    """One StableAdamW step for every tensor of the plan (two launches in total).  Returns plan.rms [n]."""
+    lib = load_library()
+    _check(lib.switchback_stable_adamw_step_multi(_ptr(plan.table), plan.n, plan.total_blocks,
+                                                  _SB_DTYPE[plan.grad_dtype], alpha, beta1, beta2, eps, lam, t,
+                                                  _ptr(plan.rms), _ptr(plan.ws), plan.ws.numel(), _stream()))
+    return plan.rms

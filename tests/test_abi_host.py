@@ -121,6 +121,21 @@ def test_bad_arguments_are_rejected_before_launch(lib):
     assert adam(fake, odd, fake, fake, 0, 100, *good, 1, null, fake, 1 << 20, null) == INVALID
     assert adam(fake, fake, fake, fake, 0, 100, *good, 1, null, fake, 8, null) == WS
     assert adam(null, null, null, null, 0, 0, *good, 1, null, null, 0, null) == 0                  # empty tensor
+    table = (sb.SbAdamwTensor * 3)(sb.SbAdamwTensor(0x1000, 0x2000, 0x3000, 0x4000, 5, 0, 0),
+                                   sb.SbAdamwTensor(0x1000, 0x2000, 0x3000, 0x4000, 1280 * 5120, 0, 0),
+                                   sb.SbAdamwTensor(0x1000, 0x2000, 0x3000, 0x4000, 100 * 1000 * 1000, 0, 0))
+    total = lib.switchback_stable_adamw_plan(table, 3)
+    assert [t.num_blocks for t in table] == [1, 1600, 2048] and [t.first_block for t in table] == [0, 1, 1601]
+    assert total == 3649
+    table[1].count = 0
+    assert lib.switchback_stable_adamw_plan(table, 3) == -INVALID
+    assert lib.switchback_stable_adamw_plan(None, 0) == 0
+    multi = lib.switchback_stable_adamw_step_multi
+    assert multi(fake, 3, 3649, 0, *good, 1, null, fake, 8 * 3649 - 1, null) == WS
+    assert multi(fake, 3, 2, 0, *good, 1, null, fake, 1 << 20, null) == INVALID                    # fewer blocks than tensors
+    assert multi(null, 3, 3649, 0, *good, 1, null, fake, 1 << 20, null) == INVALID
+    assert multi(fake, 3, 3649, 0, *good, 0, null, fake, 1 << 20, null) == INVALID
+    assert multi(null, 0, 0, 0, *good, 1, null, null, 0, null) == 0
 
 
 def test_binding_refuses_cpu_tensors():

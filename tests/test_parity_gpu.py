@@ -491,6 +491,35 @@ def test_stable_adamw_full_size_weight_and_grid_stride(oracle):
     check_adamw(oracle, 20 * 1000 * 1000 + 3, 79, True, t=5)
 
 
+def test_stable_adamw_batched_step_equals_per_tensor_steps(oracle):
+    """Many tensors in two launches: every tensor is clipped by its own RMS, bit-identical to the per-tensor entry point
+    (same workgroup partition), and within the per-tensor tolerance of the oracle."""
+    h = ADAMW_HYPER
+    counts = [1, 7, 1280, 3 * 1280, 4097, 1280 * 1280, 5, 70001, 1280 * 5120, 1024]
+    cases = [adamw_case(c, 900 + i, True, False, spike=(i % 3 == 1)) for i, c in enumerate(counts)]
+    batched, single = [], []
+    for theta, v, u, g in cases:
+        batched.append(tuple(torch.from_numpy(a.copy()).to(DEV) for a in (theta, v, u)) + (to_dev(g),))
+        single.append(tuple(torch.from_numpy(a.copy()).to(DEV) for a in (theta, v, u)) + (to_dev(g),))
+    plan = sb.AdamwPlan(batched)
+    assert plan.total_blocks >= len(counts)
+    rms = sb.stable_adamw_step_multi(plan, h["alpha"], h["beta1"], h["beta2"], h["eps"], h["lam"], 40)
+    rms_single = [sb.stable_adamw_step(th, v, u, g, h["alpha"], h["beta1"], h["beta2"], h["eps"], h["lam"], 40)
+                  for (th, v, u, g) in single]
+    torch.cuda.synchronize()
+    clipped = 0
+    for i, ((theta, v, u, g), bt, st) in enumerate(zip(cases, batched, single)):
+        for a, b in zip(bt[:3], st[:3]):
+            np.testing.assert_array_equal(host(a).view(np.uint32), host(b).view(np.uint32))
+        assert host(rms)[i].view(np.uint32) == host(rms_single[i])[0].view(np.uint32)
+        th_o, v_o, u_o, rms_o = oracle.stable_adamw_step(theta, v, u, g, h["alpha"], h["beta1"], h["beta2"], h["eps"],
+                                                         h["lam"], 40)
+        assert abs(float(host(rms)[i]) - rms_o) <= 2e-6 * rms_o + 1e-30
+        clipped += rms_o > 1.0
+        np.testing.assert_allclose(host(bt[0]), th_o, rtol=1e-5, atol=1e-9)
+    assert 0 < clipped < len(counts)                              # some tensors clipped, some not, in one launch
+
+
 def test_stable_adamw_is_deterministic_and_leaves_grad_alone():
     theta, v, u, g = adamw_case(300001, 5, True, False, True)
     outs = []
