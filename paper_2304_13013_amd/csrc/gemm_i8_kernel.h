@@ -539,10 +539,14 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
         if (OUT == OUT_BF16) {
             unsigned char *epi = smem + S * C::STAGE_BYTES + wave * C::EPI_WAVE_BYTES;
             const unsigned epi_voff = (unsigned)((lane_e / C::EPI_PIECES) * p.N + (lane_e % C::EPI_PIECES) * 8) * 2;
+            // Software pipeline over the 32-row blocks.  The patch reads of block mt are all issued first, block mt+1
+            // is converted while they travel, then the stores of block mt go out and the patch is rewritten: LDS
+            // operations of one wave execute in order, so the rewrite needs no wait for the reads before it.  The
+            // stores of an interior tile are branch-free; a branch per store would put a full wait after every read.
+            v4bf packed[C::NT * 4];
+            auto convert_block = [&](int mt) {
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-#pragma unroll
-                for (int nt = 0; nt < C::NT; ++nt) {
+                for (int nt = 0; nt < C::NT; ++nt)
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
                         v4f v;
@@ -550,24 +554,51 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
                         for (int e = 0; e < 4; ++e)
                             v[e] = (float)(acc[mt][nt][4 * q + e]) *
                                    (COLSCALE ? rscale[mt] * scol[nt][q][e] : rscale[mt]);
-                        const int piece = (nt * 4 + q) ^ (frow & 7);
-                        *reinterpret_cast<v4bf *>(epi + frow * (C::WTN * 2) + piece * 16 + fhalf * 8) =
-                            __builtin_convertvector(v, v4bf);
+                        packed[nt * 4 + q] = __builtin_convertvector(v, v4bf);
                     }
+            };
+            auto write_patch = [&]() {
+#pragma unroll
+                for (int i = 0; i < C::NT * 4; ++i) {
+                    const int piece = i ^ (frow & 7);
+                    *reinterpret_cast<v4bf *>(epi + frow * (C::WTN * 2) + piece * 16 + fhalf * 8) = packed[i];
                 }
+            };
+            convert_block(0);
+            write_patch();
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                v4u val[C::STORES_PER_BLOCK];
 #pragma unroll
                 for (int j = 0; j < C::STORES_PER_BLOCK; ++j) {
                     const int idx = j * 64 + lane_e;
                     const int prow = idx / C::EPI_PIECES, piece = idx % C::EPI_PIECES;
-                    const v4u val = *reinterpret_cast<const v4u *>(epi + prow * (C::WTN * 2) +
-                                                                   ((piece ^ (prow & 7)) << 4));
-                    const int gr = m_base + mt * 32 + prow, gc = n_base + piece * 8;
-                    // Row block j of this 32-row block starts (64 / EPI_PIECES) * j rows down; the lane's place inside
-                    // it is the per-lane constant epi_voff.
-                    const unsigned soff = (unsigned)((m_base + mt * 32 + j * (64 / C::EPI_PIECES)) * p.N + n_base) * 2;
-                    if (interior || (gr < p.M && gc < p.N))
-                        __builtin_amdgcn_raw_buffer_store_b128(val, rsrc_out, epi_voff, soff, C::STORE_NT ? 2 : 0);
+                    val[j] = *reinterpret_cast<const v4u *>(epi + prow * (C::WTN * 2) + ((piece ^ (prow & 7)) << 4));
                 }
+                if (mt + 1 < MT) convert_block(mt + 1);
+                // Row block j of this 32-row block starts (64 / EPI_PIECES) * j rows down; the lane's place inside it
+                // is the per-lane constant epi_voff.
+                if (interior) {
+#pragma unroll
+                    for (int j = 0; j < C::STORES_PER_BLOCK; ++j) {
+                        const unsigned soff =
+                            (unsigned)((m_base + mt * 32 + j * (64 / C::EPI_PIECES)) * p.N + n_base) * 2;
+                        __builtin_amdgcn_raw_buffer_store_b128(val[j], rsrc_out, epi_voff, soff, C::STORE_NT ? 2 : 0);
+                    }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < C::STORES_PER_BLOCK; ++j) {
+                        const int idx = j * 64 + lane_e;
+                        const int prow = idx / C::EPI_PIECES, piece = idx % C::EPI_PIECES;
+                        const int gr = m_base + mt * 32 + prow, gc = n_base + piece * 8;
+                        const unsigned soff =
+                            (unsigned)((m_base + mt * 32 + j * (64 / C::EPI_PIECES)) * p.N + n_base) * 2;
+                        if (gr < p.M && gc < p.N)
+                            __builtin_amdgcn_raw_buffer_store_b128(val[j], rsrc_out, epi_voff, soff,
+                                                                   C::STORE_NT ? 2 : 0);
+                    }
+                }
+                if (mt + 1 < MT) write_patch();
             }
             // Count the stores only where every one of them is certain to have been issued: an overcount would
             // loosen later waits, an undercount merely makes them stricter.
