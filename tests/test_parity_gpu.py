@@ -697,3 +697,50 @@ def test_float8_layer_is_deterministic_and_rejects_unsupported_widths():
     np.testing.assert_array_equal(bits_of(a), bits_of(b))
     with pytest.raises(sb.SwitchBackError):
         sb.forward_f8(x[:, :192].contiguous(), w[:, :192].contiguous())     # n % 128 != 0
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# maximum sizes: operands that end just below the 4 GiB reach of the kernels' 32-bit buffer offsets
+# ---------------------------------------------------------------------------------------------------------------
+
+def test_int8_product_at_the_largest_operand(oracle):
+    """aq of (M + 256) * K = 2^32 - 4096 bytes: the last tile's addresses, including the rows past M that must read as
+    zero, end just below 2^32.  Inputs are drawn on the GPU (seeded); the oracle gets the sampled rows."""
+    M, N, K = 1048319, 64, 4096
+    assert (M + 256) * K < 2 ** 32 <= (M + 257) * K
+    g = torch.Generator(device=DEV)
+    g.manual_seed(41)
+    a = torch.randint(-127, 128, (M, K), generator=g, device=DEV, dtype=torch.int8)
+    b = torch.randint(-127, 128, (N, K), generator=g, device=DEV, dtype=torch.int8)
+    sr = torch.rand(M, generator=g, device=DEV) + 0.5
+    sw = torch.tensor([0.731], device=DEV)
+    acc = sb.matmul_int8_dequant(a, None, b, None, out_dtype=torch.int32)
+    ybf = sb.matmul_int8_dequant(a, sr, b, sw, out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(42)
+    rows = np.unique(np.concatenate([[0, 255, 256, M - 256 - 63, M - 64, M - 2, M - 1], rng.integers(0, M, 40)]))
+    idx = torch.from_numpy(rows).to(DEV)
+    ref = oracle.matmul_int8(host(a[idx]), host(b))
+    np.testing.assert_array_equal(host(acc[idx]), ref)
+    y = oracle.dequantize(ref, host(sr[idx]), np.float32(0.731))
+    assert_bf16_is_rounding_within_one_ulp(bits_of(ybf[idx]), y, oracle)
+    # one more row would not be addressable: the boundary says so instead of launching
+    with pytest.raises(sb.SwitchBackError):
+        sb.matmul_int8_dequant(torch.empty((M + 1, K), dtype=torch.int8, device=DEV), sr, b, sw)
+
+
+def test_weight_gradient_at_the_largest_operand(oracle):
+    """X of (b + 256) * n * 2 bytes just below 2^32 (bf16): split-K over a million tokens, ragged last token tile."""
+    b, n, m = 1048319, 2048, 64
+    assert (b + 256) * n * 2 < 2 ** 32 <= (b + 257) * n * 2
+    g = torch.Generator(device=DEV)
+    g.manual_seed(43)
+    x = torch.randn((b, n), generator=g, device=DEV, dtype=torch.float32).to(torch.bfloat16)
+    dy = (torch.randn((b, m), generator=g, device=DEV, dtype=torch.float32) * 0.1).to(torch.bfloat16)
+    dw = sb.backward_weight(dy, x, dw_dtype=torch.float32)
+    torch.cuda.synchronize()
+    jrows = np.array([0, 31, 63])
+    ref = oracle.weight_grad(np.ascontiguousarray(bits_of(dy)[:, jrows]), bits_of(x))
+    rms = float(np.sqrt((ref ** 2).mean()))
+    got = host(dw)[jrows].astype(np.float64)
+    assert np.abs(got - ref).max() <= 1e-2 * rms
