@@ -42,6 +42,8 @@ def parse():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch three 256 MiB device-to-device copy kernels (known traffic) so that a "
                          "rocprofv3 --pmc run of this command can scale FETCH_SIZE / WRITE_SIZE")
+    ap.add_argument("--no-clocks", action="store_true",
+                    help="skip the rocm-smi clock reading (it queues about a second of extra steps)")
     ap.add_argument("--cpu-sample-rows", type=int, default=0, help="token rows of the oracle sample (0 = auto)")
     return ap.parse_args()
 
@@ -256,6 +258,25 @@ def main():
     op_sum = sum(kernels[k]["ms_per_step"] for k in in_step)
     quant_ms = kernels["quantize_rowwise"]["ms_per_step"] + kernels["quantize_tensorwise"]["ms_per_step"]
 
+    # Clocks under load: rocm-smi is read by a child process while about a second of steps is still queued.
+    clocks = None
+    if not args.no_clocks:
+        import re
+        import subprocess
+        for _ in range(max(1, int(1200.0 / max(sb_ms, 0.1)))):
+            switchback_step()
+        try:
+            txt = subprocess.run(["rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=20).stdout
+            found = {}
+            for name in ("sclk", "mclk", "fclk"):
+                m = re.search(name + r" clock level:? *\d* *:? *\(?(\d+) ?[Mm][Hh]z", txt)
+                if m:
+                    found[name + "_MHz"] = int(m.group(1))
+            clocks = found or None
+        except Exception:
+            clocks = None
+        torch.cuda.synchronize()
+
     if args.copy_calibration:
         src = torch.ones(128 << 20, dtype=torch.bfloat16, device=dev)
         dst = torch.empty_like(src)
@@ -311,6 +332,7 @@ def main():
         "kernels": kernels,
         "sum_of_kernel_ms": round(op_sum, 4),
         "quantize_share_of_kernel_time": round(quant_ms / op_sum, 4),
+        "clocks_under_load": clocks,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))
