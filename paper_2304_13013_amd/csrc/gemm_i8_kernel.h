@@ -370,6 +370,10 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
     bool first = true;
 #ifdef SB_GEMM_TIMELINE
     unsigned dbg_epi_end = 0, dbg_prologue_issued = 0;
+    unsigned dbg_epi[8] = {0, 0, 0, 0, 0, 0, 0, 0};  // epilogue: start, first block in the patch, then after each block's stores
+#define SB_EPI_STAMP(i) dbg_epi[(i) < 8 ? (i) : 7] = (unsigned)__builtin_readcyclecounter()
+#else
+#define SB_EPI_STAMP(i) do { } while (0)
 #endif
     for (int round = 0; have; ++round) {
 #ifdef SB_GEMM_TIMELINE
@@ -502,7 +506,8 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
                 reinterpret_cast<const unsigned *>(smem + S * C::STAGE_BYTES + wave * C::EPI_WAVE_BYTES);
             unsigned *dst = p.dbg + (((blockIdx.x ? 1 : 0) * 8 + wave) * 2 + round) * 208;
             for (int i = lane; i < 208; i += 52)
-                dst[i] = i == 204 ? dbg_epi_end : i == 205 ? dbg_prologue_issued : src[i];
+                dst[i] = i == 204 ? dbg_epi_end : i == 205 ? dbg_prologue_issued
+                         : (i >= 190 && i < 198) ? dbg_epi[i - 190] : src[i];
         }
         dbg_prologue_issued = (unsigned)__builtin_readcyclecounter();
 #endif
@@ -564,8 +569,10 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
                     *reinterpret_cast<v4bf *>(epi + frow * (C::WTN * 2) + piece * 16 + fhalf * 8) = packed[i];
                 }
             };
+            SB_EPI_STAMP(0);
             convert_block(0);
             write_patch();
+            SB_EPI_STAMP(1);
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
                 v4u val[C::STORES_PER_BLOCK];
@@ -599,6 +606,7 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
                     }
                 }
                 if (mt + 1 < MT) write_patch();
+                SB_EPI_STAMP(2 + mt);
             }
             // Count the stores only where every one of them is certain to have been issued: an overcount would
             // loosen later waits, an undercount merely makes them stricter.
