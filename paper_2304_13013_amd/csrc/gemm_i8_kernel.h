@@ -94,6 +94,7 @@ struct GemmI8Args {
 #ifdef SB_GEMM_TIMELINE
     unsigned *dbg;
     int dbg_point;
+    int dbg_round0;  // the two tiles of a workgroup that are stamped: its rounds dbg_round0 and dbg_round0 + 1
 #endif
 };
 
@@ -378,7 +379,7 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
     for (int round = 0; have; ++round) {
 #ifdef SB_GEMM_TIMELINE
         auto stamp = [&](int idx) {
-            if (round < 2) {
+            if ((unsigned)(round - p.dbg_round0) < 2u) {
                 const unsigned t = (unsigned)__builtin_readcyclecounter();
                 if (lane == 0)
                     *reinterpret_cast<unsigned *>(smem + S * C::STAGE_BYTES + wave * C::EPI_WAVE_BYTES + idx * 4) = t;
@@ -498,13 +499,14 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
 
         SB_STAMP(201);
 #ifdef SB_GEMM_TIMELINE
-        if (round < 2 && lane == 0)
+        const bool dbg_round = (unsigned)(round - p.dbg_round0) < 2u;
+        if (dbg_round && lane == 0)
             *reinterpret_cast<unsigned *>(smem + S * C::STAGE_BYTES + wave * C::EPI_WAVE_BYTES + 203 * 4) =
                 (unsigned)wall_clock64();
-        if (round < 2 && p.dbg && lane < 52 && (blockIdx.x == 0 || blockIdx.x == 37)) {
+        if (dbg_round && p.dbg && lane < 52 && (blockIdx.x == 0 || blockIdx.x == 37)) {
             const unsigned *src =
                 reinterpret_cast<const unsigned *>(smem + S * C::STAGE_BYTES + wave * C::EPI_WAVE_BYTES);
-            unsigned *dst = p.dbg + (((blockIdx.x ? 1 : 0) * 8 + wave) * 2 + round) * 208;
+            unsigned *dst = p.dbg + (((blockIdx.x ? 1 : 0) * 8 + wave) * 2 + (round - p.dbg_round0)) * 208;
             for (int i = lane; i < 208; i += 52)
                 dst[i] = i == 204 ? dbg_epi_end : i == 205 ? dbg_prologue_issued
                          : (i >= 190 && i < 198) ? dbg_epi[i - 190] : src[i];
