@@ -664,13 +664,29 @@ __device__ __forceinline__ void gemm_i8_dequant_body(const GemmI8Args &p) {
         gemm_i8_dequant_role<C, OUT, 8 - C::MT_LOADER, COLSCALE, MATH>(p, wave, C::MT_LOADER * 32);
 }
 
-// Launch geometry shared by the entry points: persistent grid, a multiple of the XCD count.
+// Launch geometry shared by the entry points: a persistent grid, a multiple of the XCD count, at most one workgroup
+// per compute unit.  When the tiles make only a few rounds of the full grid and do not fill the last one, the grid is
+// shrunk so that every workgroup gets the same number of tiles (645 tiles: 216 workgroups x 3 instead of 256 x 2.5):
+// the number of rounds is the same, and the kernel being power-bound, fewer active compute units run at a higher
+// clock, which measures 4-10 % faster than a last round that leaves half the GPU idle.  With many rounds the tail is
+// a small share and the full grid measures better.
 template <class C>
-inline void gemm_i8_prepare(GemmI8Args &a, int workgroups, int *grid) {
+inline void gemm_i8_prepare(GemmI8Args &a, int workgroups, int *grid, bool balance = true) {
     a.tiles_m = (a.M + C::BM - 1) / C::BM;
     a.tiles_n = (a.N + C::BN - 1) / C::BN;
     if (a.group_m <= 0) a.group_m = 8;
-    *grid = workgroups;
+    int full = workgroups & ~7;
+    if (full < 8) full = 8;
+    int g = full;
+    if (balance) {
+        const long long tiles = (long long)a.tiles_m * a.tiles_n;
+        const long long rounds = (tiles + full - 1) / full;
+        const long long per_round = (tiles + rounds - 1) / rounds;
+        if (rounds <= 4) g = (int)((per_round + 7) & ~7LL);
+        if (g > full) g = full;
+        if (g < 8) g = 8;
+    }
+    *grid = g;
 }
 
 }  // namespace sb
