@@ -24,18 +24,6 @@ SB_GEMM_F8_ENTRY(gemm_f8_a5b5_bf16, OUT_BF16, 1, 1)
 SB_GEMM_F8_ENTRY(gemm_f8_a5b5_f32, OUT_F32, 1, 1)
 #undef SB_GEMM_F8_ENTRY
 
-int cached_num_cu() {
-    static int n = 0;
-    if (n == 0) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-            n = prop.multiProcessorCount;
-        if (n <= 0) n = 256;
-    }
-    return n;
-}
-
 }  // namespace
 
 hipError_t launch_gemm_f8_dequant(const uint8_t *aq, int fmt_a, const float *state_row, const uint8_t *bq, int fmt_b,
@@ -56,7 +44,7 @@ hipError_t launch_gemm_f8_dequant(const uint8_t *aq, int fmt_a, const float *sta
     GemmI8Args args{reinterpret_cast<const int8_t *>(aq), reinterpret_cast<const int8_t *>(bq), state_row, state_tensor,
                     nullptr, out, (int)M, (int)N, (int)K, 0, 0, 8};
     int grid = 0;
-    gemm_i8_prepare<F8Cfg>(args, cached_num_cu(), &grid);
+    gemm_i8_prepare<F8Cfg>(args, num_compute_units(), &grid);
     kernels[which]<<<grid, F8Cfg::THREADS, F8Cfg::LDS_BYTES, stream>>>(args);
     return hipGetLastError();
 }

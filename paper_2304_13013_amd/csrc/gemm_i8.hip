@@ -29,7 +29,24 @@ SB_GEMM_I8_ENTRY_Q(gemm_i8q_k64_f32, K64, OUT_F32)
 #undef SB_GEMM_I8_ENTRY_Q
 #undef SB_GEMM_I8_ENTRY
 
-int cached_num_cu() {
+template <class C>
+hipError_t launch(void (*kernel)(GemmI8Args), bool *attr_set, GemmI8Args args, hipStream_t stream) {
+    if (!*attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+        if (e != hipSuccess) return e;
+        *attr_set = true;
+    }
+    int grid = 0;
+    gemm_i8_prepare<C>(args, num_compute_units(), &grid);
+    kernel<<<grid, C::THREADS, C::LDS_BYTES, stream>>>(args);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// Compute units of the current device (queried once per process; the library serves one GPU).
+int num_compute_units() {
     static int n = 0;
     if (n == 0) {
         int dev = 0;
@@ -40,22 +57,6 @@ int cached_num_cu() {
     }
     return n;
 }
-
-template <class C>
-hipError_t launch(void (*kernel)(GemmI8Args), bool *attr_set, GemmI8Args args, hipStream_t stream) {
-    if (!*attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
-        if (e != hipSuccess) return e;
-        *attr_set = true;
-    }
-    int grid = 0;
-    gemm_i8_prepare<C>(args, cached_num_cu(), &grid);
-    kernel<<<grid, C::THREADS, C::LDS_BYTES, stream>>>(args);
-    return hipGetLastError();
-}
-
-}  // namespace
 
 hipError_t launch_gemm_i8_dequant(const int8_t *aq, const float *state_row, const int8_t *bq,
                                   const float *state_tensor, const float *state_col, int64_t M, int64_t N,

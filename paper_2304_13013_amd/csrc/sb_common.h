@@ -43,6 +43,7 @@ hipError_t launch_quantize_rowwise_f8(const void *x, int64_t rows, int64_t cols,
                                       hipStream_t stream);
 hipError_t launch_quantize_tensorwise_f8(const void *w, int64_t rows, int64_t cols, int fmt, uint8_t *codes,
                                          uint8_t *codes_t, float *state, unsigned int *partials, hipStream_t stream);
+int num_compute_units();
 // state_col == nullptr: tensor-wise weight state (state_tensor[0]); else one state per output column (SwitchBackQ).
 hipError_t launch_gemm_i8_dequant(const int8_t *aq, const float *state_row, const int8_t *bq,
                                   const float *state_tensor, const float *state_col, int64_t M, int64_t N,
