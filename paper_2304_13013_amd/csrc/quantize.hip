@@ -213,7 +213,39 @@ __global__ __launch_bounds__(256) void absmax_partial_kernel(const v4u *__restri
 // The transposed copy goes through LDS so that both code matrices leave in 128-byte row segments while W is read
 // once in this pass.
 constexpr int kTile = 128;
-constexpr int kTileStride = kTile + 16;  // bytes per LDS row (keeps 16-byte alignment, staggers banks)
+// The tile's codes sit in LDS row-major as dwords (4 codes each), 33 dwords per row and the lower half of the rows
+// shifted by another 8, which makes the transposing read-out below free of bank conflicts.
+constexpr int kTileRowDwords = kTile / 4 + 1;
+constexpr int kTileDwords = kTile * kTileRowDwords + 8;
+__device__ __forceinline__ int tile_dword(int row, int dcol) { return row * kTileRowDwords + ((row >> 6) << 3) + dcol; }
+
+// Writes the transposed tile: q_t[c0 + c, r0 + r] = tile[r, c].  Thread t takes the four columns 4*(t/8).. and the
+// sixteen rows 16*(t%8)..: sixteen dword reads, 4x4 byte transposes with v_perm_b32, four 16-byte stores; eight
+// consecutive lanes cover 128 contiguous bytes of one transposed row.
+__device__ __forceinline__ void store_tile_transposed(const unsigned int *tile, int8_t *__restrict__ q_t, int rows,
+                                                      int cols, int r0, int c0) {
+    const int rb = threadIdx.x & 7, cg = threadIdx.x >> 3;
+    unsigned int piece[4][4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const unsigned int a0 = tile[tile_dword(16 * rb + 4 * g + 0, cg)], a1 = tile[tile_dword(16 * rb + 4 * g + 1, cg)];
+        const unsigned int a2 = tile[tile_dword(16 * rb + 4 * g + 2, cg)], a3 = tile[tile_dword(16 * rb + 4 * g + 3, cg)];
+        // v_perm_b32: selector bytes 0-3 pick from the second operand, 4-7 from the first.
+        const unsigned int lo01 = __builtin_amdgcn_perm(a1, a0, 0x05010400u), hi01 = __builtin_amdgcn_perm(a1, a0, 0x07030602u);
+        const unsigned int lo23 = __builtin_amdgcn_perm(a3, a2, 0x05010400u), hi23 = __builtin_amdgcn_perm(a3, a2, 0x07030602u);
+        piece[0][g] = __builtin_amdgcn_perm(lo23, lo01, 0x05040100u);
+        piece[1][g] = __builtin_amdgcn_perm(lo23, lo01, 0x07060302u);
+        piece[2][g] = __builtin_amdgcn_perm(hi23, hi01, 0x05040100u);
+        piece[3][g] = __builtin_amdgcn_perm(hi23, hi01, 0x07060302u);
+    }
+    const int r = r0 + 16 * rb;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int c = c0 + 4 * cg + k;
+        if (c < cols && r < rows)
+            *reinterpret_cast<v4u *>(q_t + (int64_t)c * rows + r) = v4u{piece[k][0], piece[k][1], piece[k][2], piece[k][3]};
+    }
+}
 
 template <int CODE>
 __global__ __launch_bounds__(256) void quantize_tensorwise_kernel(const v4u *__restrict__ w, int rows, int cols,
@@ -223,7 +255,7 @@ __global__ __launch_bounds__(256) void quantize_tensorwise_kernel(const v4u *__r
                                                                   const unsigned int *__restrict__ partials,
                                                                   int npartials) {
     __shared__ unsigned int wave_max[4];
-    __shared__ __attribute__((aligned(16))) unsigned char tile_t[kTile * kTileStride];
+    __shared__ unsigned int tile[kTileDwords];
     unsigned int m = 0;
     for (int i = threadIdx.x; i < npartials; i += 256) m = max(m, partials[i]);
     m = wave_max_u32(m);
@@ -245,25 +277,14 @@ __global__ __launch_bounds__(256) void quantize_tensorwise_kernel(const v4u *__r
             const v2u codes = quantize_chunk<CODE>(w[(int64_t)r * chunks_per_row + (c >> 3)], t);
             *reinterpret_cast<v2u *>(q + (int64_t)r * cols + c) = codes;
             if (q_t) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    tile_t[(lc + j) * kTileStride + lr] = (unsigned char)(codes.x >> (8 * j));
-                    tile_t[(lc + 4 + j) * kTileStride + lr] = (unsigned char)(codes.y >> (8 * j));
-                }
+                tile[tile_dword(lr, lc >> 2)] = codes.x;
+                tile[tile_dword(lr, (lc >> 2) + 1)] = codes.y;
             }
         }
     }
     if (!q_t) return;  // uniform across the grid
     __syncthreads();
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int id = threadIdx.x + 256 * i;
-        const int lc = id >> 3, lr = (id & 7) << 4;  // one 16-byte piece of a transposed row
-        const int c = c0 + lc, r = r0 + lr;
-        if (c < cols && r < rows)
-            *reinterpret_cast<v4u *>(q_t + (int64_t)c * rows + r) =
-                *reinterpret_cast<const v4u *>(tile_t + lc * kTileStride + lr);
-    }
+    store_tile_transposed(tile, q_t, rows, cols, r0, c0);
 }
 
 // ---- column-wise quantization fused with a transpose (SwitchBackQ backward) -----------------------------------
@@ -295,7 +316,7 @@ __global__ __launch_bounds__(256) void quantize_colwise_transpose_kernel(const v
                                                                          const unsigned short *__restrict__ partials,
                                                                          int nparts) {
     __shared__ float tcol[kTile];
-    __shared__ __attribute__((aligned(16))) unsigned char tile_t[kTile * kTileStride];
+    __shared__ unsigned int tile[kTileDwords];
     const int r0 = blockIdx.y * kTile, c0 = blockIdx.x * kTile;
     if (threadIdx.x < kTile) {
         const int c = c0 + threadIdx.x;
@@ -319,25 +340,18 @@ __global__ __launch_bounds__(256) void quantize_colwise_transpose_kernel(const v
         if (r < rows && c < cols) {
             const v4u v = w[(int64_t)r * chunks_per_row + (c >> 3)];
             const unsigned int d[4] = {v.x, v.y, v.z, v.w};
+            unsigned int code[8];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                tile_t[(lc + 2 * j) * kTileStride + lr] =
-                    (unsigned char)code_bits(__uint_as_float(d[j] << 16), tcol[lc + 2 * j]);
-                tile_t[(lc + 2 * j + 1) * kTileStride + lr] =
-                    (unsigned char)code_bits(__uint_as_float(d[j] & 0xffff0000u), tcol[lc + 2 * j + 1]);
+                code[2 * j] = code_bits(__uint_as_float(d[j] << 16), tcol[lc + 2 * j]) & 0xffu;
+                code[2 * j + 1] = code_bits(__uint_as_float(d[j] & 0xffff0000u), tcol[lc + 2 * j + 1]) & 0xffu;
             }
+            tile[tile_dword(lr, lc >> 2)] = code[0] | (code[1] << 8) | (code[2] << 16) | (code[3] << 24);
+            tile[tile_dword(lr, (lc >> 2) + 1)] = code[4] | (code[5] << 8) | (code[6] << 16) | (code[7] << 24);
         }
     }
     __syncthreads();
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int id = threadIdx.x + 256 * i;
-        const int lc = id >> 3, lr = (id & 7) << 4;  // one 16-byte piece of a transposed row
-        const int c = c0 + lc, r = r0 + lr;
-        if (c < cols && r < rows)
-            *reinterpret_cast<v4u *>(q_t + (int64_t)c * rows + r) =
-                *reinterpret_cast<const v4u *>(tile_t + lc * kTileStride + lr);
-    }
+    store_tile_transposed(tile, q_t, rows, cols, r0, c0);
 }
 
 // Row-wise dequantization of the memory-efficient variant (SwitchBackM, the appendix algorithm that saves only the
