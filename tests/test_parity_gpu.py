@@ -744,3 +744,36 @@ def test_weight_gradient_at_the_largest_operand(oracle):
     rms = float(np.sqrt((ref ** 2).mean()))
     got = host(dw)[jrows].astype(np.float64)
     assert np.abs(got - ref).max() <= 1e-2 * rms
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# repeatability at full size: the GEMM kernels order their memory traffic with hand-counted waits, so the same launch
+# is repeated many times on the benchmark's shapes and every result must equal the first bit for bit
+# ---------------------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("layer", [1, 2, 3])
+def test_products_are_repeatable_at_full_size(layer):
+    L = I.CONFIGS["vit_h14"].layers[layer]
+    g = torch.Generator(device=DEV)
+    g.manual_seed(50 + layer)
+    x = torch.randn((L.b, L.n), generator=g, device=DEV).to(torch.bfloat16)
+    w = (torch.randn((L.m, L.n), generator=g, device=DEV) * L.n ** -0.5).to(torch.bfloat16)
+    dy = (torch.randn((L.b, L.m), generator=g, device=DEV) * 0.1).to(torch.bfloat16)
+    bufs = sb.LayerBuffers(L.b, L.n, L.m, DEV)
+    y0, _ = sb.forward(x, w, bufs=bufs)
+    dx0 = sb.backward_input(dy, bufs)
+    dw0 = sb.backward_weight(dy, x, bufs)
+    y, dx, dw = torch.empty_like(y0), torch.empty_like(dx0), torch.empty_like(dw0)
+    for rep in range(25):
+        y.fill_(1.0), dx.fill_(1.0), dw.fill_(1.0)
+        sb.matmul_int8_dequant(bufs.xq, bufs.state_x, bufs.wq, bufs.state_w, out=y)
+        sb.matmul_int8_dequant(bufs.gq, bufs.state_g, bufs.wq_t, bufs.state_w, out=dx)
+        sb.backward_weight(dy, x, bufs, dw=dw)
+        assert torch.equal(y, y0) and torch.equal(dx, dx0) and torch.equal(dw, dw0), "repetition %d differs" % rep
+    y8, _ = sb.forward_f8(x, w, bufs=bufs)
+    y8b = torch.empty_like(y8)
+    u8 = lambda q: q.view(torch.uint8)
+    for rep in range(25):
+        y8b.fill_(1.0)
+        sb.matmul_f8_dequant(u8(bufs.xq), sb.SB_E4M3, bufs.state_x, u8(bufs.wq), sb.SB_E4M3, bufs.state_w, out=y8b)
+        assert torch.equal(y8b, y8), "float8 repetition %d differs" % rep
