@@ -35,7 +35,10 @@
 //     many outstanding".
 //   * The epilogue transposes the bf16 results through a wave-private, XOR-swizzled LDS patch and stores 16 bytes
 //     per lane, covering whole 128-byte row segments, with non-temporal buffer stores (the output must not evict
-//     the operand panels the other workgroups of the XCD are reading from L2).
+//     the operand panels the other workgroups of the XCD are reading from L2).  It is software-pipelined over the
+//     32-row blocks of the wave tile: the patch reads of one block are in flight while the next block is converted.
+//   * The same pipeline serves the float8 product (MATH_F8): one v_mfma_f32_32x32x64_f8f6f4 per 64 k-values, an
+//     operand fragment being the two 16-byte LDS reads that two int8 k-steps would issue.
 //   * SB_GEMM_TIMELINE (off in the library) compiles in cycle stamps at the code points of the main loop; the
 //     figures quoted above come from them.
 #pragma once
