@@ -101,14 +101,20 @@ struct GemmI8Args {
 #endif
 };
 
-// Output tile visited by workgroup `wg` in its `round`-th iteration.  Workgroups are dealt to XCDs round-robin,
-// so the nwg/8 workgroups with equal wg % 8 share an L2; they get consecutive ids in an order that walks groups
-// of group_m tile-rows column by column.
+// Output tile visited by workgroup `wg` in its `round`-th iteration.  Tiles are numbered along groups of group_m
+// tile-rows, column by column inside a group.  Workgroups are dealt to XCDs round-robin, so the nwg/8 workgroups with
+// equal wg % 8 share an L2: each XCD owns one contiguous eighth of the numbering and works through it 32 (nwg/8) tiles
+// per round, so that it sweeps the columns of its own row groups and finds their token-side panels in its L2 again in
+// the next round (measured: 6 % less traffic from beyond L2 than dealing the numbering to the XCDs in chunks, same
+// speed; a 4 MB L2 barely holds the twelve panels of one round).
 __device__ __forceinline__ bool gemm_tile_of(int wg, int round, int nwg, int tiles_m, int tiles_n, int group_m,
                                              int *tm, int *tn) {
     const int per_xcd = nwg >> 3;
-    const int id = (round * 8 + (wg & 7)) * per_xcd + (wg >> 3);
-    if (id >= tiles_m * tiles_n) return false;
+    const int total = tiles_m * tiles_n;
+    const int x = wg & 7;
+    const int lo = (int)((long long)x * total / 8), hi = (int)((long long)(x + 1) * total / 8);
+    const int id = lo + round * per_xcd + (wg >> 3);
+    if (id >= hi) return false;
     const int per_group = group_m * tiles_n;
     const int first_m = (id / per_group) * group_m;
     const int group_rows = min(tiles_m - first_m, group_m);
