@@ -26,8 +26,8 @@ PEAK = {"hbm_GBps": 8000.0, "int8_TOPs": 5000.0, "bf16_TFLOPs": 2500.0}
 # copy kernels of known size; summary and commands in profiles/bench_vit_h14_hbm_traffic.md).  Not re-measured at run
 # time; null for other workloads.
 TRAFFIC_BYTES_PER_LAUNCH_VIT_H14 = {
-    "gemm_int8_dequant": 333.6e6 + 168.5e6,        # 8 launches per step; algorithmic mean 257.6e6
-    "gemm_bf16_weight_grad": 755.7e6 + 97.9e6,     # 4 launches per step, fp32 split-K partials included
+    "gemm_int8_dequant": 324.3e6 + 169.1e6,        # 8 launches per step; algorithmic mean 257.6e6
+    "gemm_bf16_weight_grad": 743.6e6 + 97.9e6,     # 4 launches per step, fp32 split-K partials included
     "quantize_rowwise": 253.2e6,                   # 8 launches per step
 }
 
