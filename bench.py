@@ -156,6 +156,27 @@ def main():
     sb_ms, sb_wall_ms = timed(switchback_step, args.steps, args.warmup)
     bf_ms, _ = timed(bf16_step, args.steps, args.warmup)
     requant_ms, _ = timed(switchback_step_requant, max(3, args.steps // 2), 2)
+
+    # Per layer: forward + input gradient + weight gradient of that layer alone, back to back, both ways.
+    per_layer = []
+    for t in layers:
+        def one_sb(t=t):
+            sb.forward(t["x"], t["w"], bufs=t["bufs"], y=t["y"])
+            sb.backward_input(t["dy"], t["bufs"], dx=t["dx"])
+            sb.backward_weight(t["dy"], t["x"], t["bufs"], dw=t["dw"])
+
+        def one_bf(t=t):
+            torch.matmul(t["x"], t["w"].t(), out=t["y"])
+            torch.matmul(t["dy"], t["w"], out=t["dx"])
+            torch.matmul(t["dy"].t(), t["x"], out=t["dw"])
+
+        n_rep = max(5, args.steps // 2)
+        a, _ = timed(one_sb, n_rep, 2)
+        c, _ = timed(one_bf, n_rep, 2)
+        L = t["L"]
+        per_layer.append({"layer": L.name, "b": L.b, "n": L.n, "m": L.m, "switchback_ms": round(a, 4),
+                          "bf16_linear_ms": round(c, 4), "speedup": round(c / a, 4),
+                          "TFLOPs": round(6.0 * L.b * L.n * L.m / a / 1e9, 1)})
     variant_m_ms, _ = timed(switchback_m_step, max(3, args.steps // 2), 2)
     variant_q_ms, _ = timed(switchback_q_step, max(3, args.steps // 2), 2)
     q_bufs.clear()
@@ -328,6 +349,7 @@ def main():
         "ms_per_step_switchback_m": round(variant_m_ms, 4),
         "ms_per_step_switchback_q": round(variant_q_ms, 4),
         "ms_per_step_switchback_float8": None if variant_f8_ms is None else round(variant_f8_ms, 4),
+        "per_layer": per_layer,
         "roofline": roofline,
         "kernels": kernels,
         "sum_of_kernel_ms": round(op_sum, 4),
