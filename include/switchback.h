@@ -1,6 +1,7 @@
 /*
  * libswitchback -- the SwitchBack int8 linear layer (arxiv 2304.13013, Section 2.2.1, Algorithm 1) for one
- * AMD MI355X (gfx950), as a C ABI.
+ * AMD MI355X (gfx950), as a C ABI.  Declared after the five calls of Algorithm 1: the layer's variants from the same
+ * paper (SwitchBackM, SwitchBackQ, float8) and its optimizer (StableAdamW), each with the passage it follows.
  *
  * Notation (Section 2.2.1 "Notation"): X [b,n] inputs, W [m,n] weights (an nn.Linear weight, out x in),
  * Y = X W^T [b,m]; dY [b,m] the gradient of the loss w.r.t. Y, dX = dY W [b,n], dW = dY^T X [m,n];
