@@ -263,7 +263,8 @@ def test_switchback_q_ragged_shapes(oracle, b, n, m):
     check_layer_q(oracle, d)
 
 
-@pytest.mark.parametrize("config,layer", [("vit_h14", 2), ("vit_h14", 3)])
+@pytest.mark.parametrize("config,layer", [("vit_b16", 0), ("vit_b16", 1), ("vit_l14", 1), ("vit_l14", 3), ("vit_h14", 2),
+                                          ("vit_h14", 3), ("outlier", 0)])
 def test_switchback_q_full_size_sampled(oracle, config, layer):
     L = I.CONFIGS[config].layers[layer]
     d = I.make_layer_inputs(config, layer)
@@ -679,7 +680,8 @@ def test_float8_layer_ragged_shapes(oracle, b, n, m):
     check_layer_f8(oracle, d)
 
 
-@pytest.mark.parametrize("config,layer", [("vit_h14", 2), ("vit_h14", 3), ("outlier", 0)])
+@pytest.mark.parametrize("config,layer", [("vit_b16", 0), ("vit_b16", 1), ("vit_l14", 1), ("vit_l14", 3), ("vit_h14", 0),
+                                          ("vit_h14", 2), ("vit_h14", 3), ("outlier", 0), ("outlier", 1)])
 def test_float8_layer_full_size_sampled(oracle, config, layer):
     L = I.CONFIGS[config].layers[layer]
     d = I.make_layer_inputs(config, layer)
