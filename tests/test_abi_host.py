@@ -142,3 +142,13 @@ def test_binding_refuses_cpu_tensors():
     import torch
     with pytest.raises(sb.SwitchBackError):
         sb.quantize_rowwise(torch.zeros(4, 64, dtype=torch.bfloat16))
+
+
+def test_a_missing_library_is_an_error_not_a_fallback(monkeypatch):
+    """The product path has no CPU fallback: without the built library every entry point of the binding raises."""
+    monkeypatch.setattr(sb, "_lib", None)
+    monkeypatch.setattr(sb, "LIB_PATH", os.path.join(ROOT, "paper_2304_13013_amd", "no_such_library.so"))
+    with pytest.raises(sb.SwitchBackError):
+        sb.load_library()
+    with pytest.raises(sb.SwitchBackError):
+        sb.workspace_bytes(sb.SB_OP_FORWARD, 8, 64, 64)
