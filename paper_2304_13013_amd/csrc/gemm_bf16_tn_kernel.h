@@ -31,10 +31,6 @@ struct GemmBf16Args {
     int b, n, m;
     int tiles_m, tiles_n, splits, k_per_split;  // k_per_split is a multiple of the stage length
     int out_bf16;
-#ifdef SB_GEMM_TIMELINE
-    unsigned *dbg;
-    int dbg_point;
-#endif
 };
 
 template <int STAGES_ = 2, int LOADERS_ = 4, int MT_LOADER_ = 4, int BKT_ = 64>
@@ -205,15 +201,6 @@ __device__ __forceinline__ void gemm_bf16_tn_role(const GemmBf16Args &p, const i
     }
 
     for (int round = 0; have; ++round) {
-#ifdef SB_GEMM_TIMELINE
-        auto stamp = [&](int idx) {
-            if (round < 2) {
-                const unsigned t = (unsigned)__builtin_readcyclecounter();
-                if (lane == 0)
-                    *reinterpret_cast<unsigned *>(smem + S * C::STAGE_BYTES + wave * C::EPI_WAVE_BYTES + idx * 4) = t;
-            }
-        };
-#endif
         v16f acc[MT][C::NT];
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
@@ -235,25 +222,19 @@ __device__ __forceinline__ void gemm_bf16_tn_role(const GemmBf16Args &p, const i
                 if (handed_over) {
                     // Stage hand-over (see the int8 kernel): this wave's reads of stage kt are retired, stage kt+1
                     // has landed, the freed stage may be refilled.
-                    if (kt < 50) SB_STAMP_AT(12, kt * 4 + 0);
                     if (loader) wait_stage<C::LPW, 0>(issued_upto - (kt + 1));
-                    if (kt < 50) SB_STAMP_AT(13, kt * 4 + 0);
                     wait_lds_reads();
-                    if (kt < 50) SB_STAMP_AT(14, kt * 4 + 0);
                     block_barrier();
-                    if (kt < 50) SB_STAMP(kt * 4 + 3);
                     if (loader && kt + S < KT) issue_stage(kt + S);
                     issued_upto = min(KT - 1, kt + S);
                 }
                 const int cur = kk & 1, nxt = (kk + 1) & 1;
                 const int next_kt = last_group ? kt + 1 : kt, next_kk = last_group ? 0 : kk + 1;
                 int landed = 0;
-                if (kt < 50) SB_STAMP_AT(kk * 3 + 0, kt * 4 + 0);
 #pragma unroll
                 for (int idx = 0; idx < MT * C::NT; ++idx) {
                     const int mt = idx / C::NT, nt = idx % C::NT;
                     const int need = idx == 0 ? 2 : idx == 1 ? 3 : 3 + idx / 2;
-                    if (idx == 1 && kt < 50) SB_STAMP_AT(kk * 3 + 1, kt * 4 + 0);
                     if (need > landed) {
                         if (!has_next)
                             wait_frags_at_most(NFRAG - need);
@@ -267,7 +248,6 @@ __device__ __forceinline__ void gemm_bf16_tn_role(const GemmBf16Args &p, const i
                     if (idx < NFRAG && has_next) issue_frag_read(idx, nxt, next_kt, next_kk);
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                if (kt < 50) SB_STAMP_AT(kk * 3 + 2, kt * 4 + 0);
             }
         };
         if (KT > 0) {
@@ -279,14 +259,6 @@ __device__ __forceinline__ void gemm_bf16_tn_role(const GemmBf16Args &p, const i
             k_tile(KT - 1, std::true_type());
         }
 
-#ifdef SB_GEMM_TIMELINE
-        if (round < 2 && p.dbg && lane < 52 && (blockIdx.x == 0 || blockIdx.x == 37)) {
-            const unsigned *src =
-                reinterpret_cast<const unsigned *>(smem + S * C::STAGE_BYTES + wave * C::EPI_WAVE_BYTES);
-            unsigned *dst = p.dbg + (((blockIdx.x ? 1 : 0) * 8 + wave) * 2 + round) * 208;
-            for (int i = lane; i < 208; i += 52) dst[i] = src[i];
-        }
-#endif
         const int m_base = tm * C::BM + wm0, n_base = tn * C::BN + wn0;
         const int this_split = split;
 

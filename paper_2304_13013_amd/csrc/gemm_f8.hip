@@ -2,6 +2,8 @@
 // gemm_i8_kernel.h with the float8 arithmetic selected).
 #include "gemm_i8_kernel.h"
 
+#include <atomic>
+
 namespace sb {
 namespace {
 
@@ -33,13 +35,13 @@ hipError_t launch_gemm_f8_dequant(const uint8_t *aq, int fmt_a, const float *sta
     typedef void (*Kernel)(GemmI8Args);
     static const Kernel kernels[8] = {gemm_f8_a4b4_bf16, gemm_f8_a4b4_f32, gemm_f8_a5b4_bf16, gemm_f8_a5b4_f32,
                                       gemm_f8_a4b5_bf16, gemm_f8_a4b5_f32, gemm_f8_a5b5_bf16, gemm_f8_a5b5_f32};
-    static bool attr_set[8] = {false, false, false, false, false, false, false, false};
+    static std::atomic<bool> attr_set[8];  // zero-initialized; a racing second set is harmless
     const int which = (fmt_b ? 4 : 0) + (fmt_a ? 2 : 0) + (out_dtype == SB_BF16 ? 0 : 1);
-    if (!attr_set[which]) {
+    if (!attr_set[which].load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernels[which]),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, F8Cfg::LDS_BYTES);
         if (e != hipSuccess) return e;
-        attr_set[which] = true;
+        attr_set[which].store(true, std::memory_order_release);
     }
     GemmI8Args args{reinterpret_cast<const int8_t *>(aq), reinterpret_cast<const int8_t *>(bq), state_row, state_tensor,
                     nullptr, out, (int)M, (int)N, (int)K, 0, 0, 8};

@@ -1,6 +1,8 @@
 // Host-side dispatch of the int8 GEMM with dequantizing epilogue (kernel: gemm_i8_kernel.h).
 #include "gemm_i8_kernel.h"
 
+#include <atomic>
+
 namespace sb {
 namespace {
 
@@ -30,12 +32,12 @@ SB_GEMM_I8_ENTRY_Q(gemm_i8q_k64_f32, K64, OUT_F32)
 #undef SB_GEMM_I8_ENTRY
 
 template <class C>
-hipError_t launch(void (*kernel)(GemmI8Args), bool *attr_set, GemmI8Args args, hipStream_t stream) {
-    if (!*attr_set) {
+hipError_t launch(void (*kernel)(GemmI8Args), std::atomic<bool> *attr_set, GemmI8Args args, hipStream_t stream) {
+    if (!attr_set->load(std::memory_order_acquire)) {  // setting it twice (two host threads racing) is harmless
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
         if (e != hipSuccess) return e;
-        *attr_set = true;
+        attr_set->store(true, std::memory_order_release);
     }
     int grid = 0;
     gemm_i8_prepare<C>(args, num_compute_units(), &grid);
@@ -45,15 +47,18 @@ hipError_t launch(void (*kernel)(GemmI8Args), bool *attr_set, GemmI8Args args, h
 
 }  // namespace
 
-// Compute units of the current device (queried once per process; the library serves one GPU).
+// Compute units of the current device (queried once per process; the library serves one GPU).  Host threads may race
+// to the first query: both store the same value.
 int num_compute_units() {
-    static int n = 0;
+    static std::atomic<int> cached{0};
+    int n = cached.load(std::memory_order_relaxed);
     if (n == 0) {
         int dev = 0;
         hipDeviceProp_t prop;
         if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
             n = prop.multiProcessorCount;
-        if (n <= 0) n = 256;
+        if (n <= 0) n = 256;  // no device visible (host-only callers sizing a workspace): an MI355X has 256
+        cached.store(n, std::memory_order_relaxed);
     }
     return n;
 }
@@ -64,14 +69,14 @@ hipError_t launch_gemm_i8_dequant(const int8_t *aq, const float *state_row, cons
     if (M == 0 || N == 0) return hipSuccess;
     GemmI8Args args{aq, bq, state_row, state_tensor, state_col, out, (int)M, (int)N, (int)K, 0, 0, 8};
     if (state_col != nullptr && out_dtype != SB_I32_RAW) {
-        static bool q_attr_set[4] = {false, false, false, false};
+        static std::atomic<bool> q_attr_set[4];  // zero-initialized
         if (K % 128 == 0)
             return out_dtype == SB_BF16 ? launch<K128Q>(gemm_i8q_k128_bf16, &q_attr_set[0], args, stream)
                                         : launch<K128Q>(gemm_i8q_k128_f32, &q_attr_set[1], args, stream);
         return out_dtype == SB_BF16 ? launch<K64>(gemm_i8q_k64_bf16, &q_attr_set[2], args, stream)
                                     : launch<K64>(gemm_i8q_k64_f32, &q_attr_set[3], args, stream);
     }
-    static bool attr_set[6] = {false, false, false, false, false, false};
+    static std::atomic<bool> attr_set[6];  // zero-initialized
     const bool wide = K % 128 == 0;
     switch (out_dtype) {
         case SB_BF16:

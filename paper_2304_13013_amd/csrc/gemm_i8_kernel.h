@@ -39,8 +39,7 @@
 //     32-row blocks of the wave tile: the patch reads of one block are in flight while the next block is converted.
 //   * The same pipeline serves the float8 product (MATH_F8): one v_mfma_f32_32x32x64_f8f6f4 per 64 k-values, an
 //     operand fragment being the two 16-byte LDS reads that two int8 k-steps would issue.
-//   * SB_GEMM_TIMELINE (off in the library) compiles in cycle stamps at the code points of the main loop; the
-//     figures quoted above come from them.
+//   * The cycle figures quoted above come from s_memtime stamps compiled into a working copy of this kernel.
 #pragma once
 #include "sb_common.h"
 #include <type_traits>
@@ -94,11 +93,6 @@ struct GemmI8Args {
     int M, N, K;  // M*K and N*K must stay below 2^32 (32-bit buffer offsets)
     int tiles_m, tiles_n;
     int group_m;  // tile rows per group of the tile walk
-#ifdef SB_GEMM_TIMELINE
-    unsigned *dbg;
-    int dbg_point;
-    int dbg_round0;  // the two tiles of a workgroup that are stamped: its rounds dbg_round0 and dbg_round0 + 1
-#endif
 };
 
 // Output tile visited by workgroup `wg` in its `round`-th iteration.  Tiles are numbered along groups of group_m
@@ -157,13 +151,6 @@ __device__ __forceinline__ void wait_stage(int later) {
     }
 }
 
-#ifdef SB_GEMM_TIMELINE
-#define SB_STAMP_AT(pt, idx) do { if (p.dbg_point == (pt)) stamp(idx); } while (0)
-#define SB_STAMP(idx) stamp(idx)
-#else
-#define SB_STAMP_AT(pt, idx) do { } while (0)
-#define SB_STAMP(idx) do { } while (0)
-#endif
 
 // What one wave does: an (MT*32) x 64 part of the workgroup's tile, rows from wm0.  Every role runs the same
 // sequence of barriers.
@@ -378,23 +365,7 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
     bool have = segment_of(0, cs);
     int g = 0;  // global index of the stage the MFMAs work on
     bool first = true;
-#ifdef SB_GEMM_TIMELINE
-    unsigned dbg_epi_end = 0, dbg_prologue_issued = 0;
-    unsigned dbg_epi[8] = {0, 0, 0, 0, 0, 0, 0, 0};  // epilogue: start, first block in the patch, then after each block's stores
-#define SB_EPI_STAMP(i) dbg_epi[(i) < 8 ? (i) : 7] = (unsigned)__builtin_readcyclecounter()
-#else
-#define SB_EPI_STAMP(i) do { } while (0)
-#endif
     for (int round = 0; have; ++round) {
-#ifdef SB_GEMM_TIMELINE
-        auto stamp = [&](int idx) {
-            if ((unsigned)(round - p.dbg_round0) < 2u) {
-                const unsigned t = (unsigned)__builtin_readcyclecounter();
-                if (lane == 0)
-                    *reinterpret_cast<unsigned *>(smem + S * C::STAGE_BYTES + wave * C::EPI_WAVE_BYTES + idx * 4) = t;
-            }
-        };
-#endif
         AccT acc[MT][C::NT];
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
@@ -442,7 +413,6 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
             for (int i = 0; i < NFRAG; ++i) issue_frag_read(i, 0, g % S, 0);
             first = false;
         }
-        SB_STAMP(200);
 
         // One k-tile (stage g).  Its last k-step group hands the stage over and already reads the next stage's first
         // fragments, also when that stage belongs to the next segment.  A stage that ends the fragment pipeline (the
@@ -460,18 +430,13 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
                     // Hand-over: the fragments of this last k-step of the stage are in (or on their way to)
                     // registers.  Retire this wave's LDS reads, make sure the next stage has landed, then refill
                     // the freed slot.
-                    SB_STAMP_AT(12, kt * 4 + 0);
                     if (loader) wait_slot_landed(next_slot);
-                    SB_STAMP_AT(13, kt * 4 + 0);
                     wait_lds_reads();
-                    SB_STAMP_AT(14, kt * 4 + 0);
                     block_barrier();
-                    SB_STAMP(kt * 4 + 3);
                     issue_next();
                 }
                 const int cur = kk & 1, nxt = (kk + 1) & 1;
                 const int read_slot = last_group ? next_slot : slot, next_kk = last_group ? 0 : kk + 1;
-                SB_STAMP_AT(kk * 3 + 0, kt * 4 + 0);
                 int landed = 0;  // fragments of this group known to have landed
 #pragma unroll
                 for (int idx = 0; idx < MT * C::NT; ++idx) {
@@ -489,7 +454,6 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
                         for (int i = landed; i < need; ++i) pin_frag(i, cur);
                         landed = need;
                     }
-                    if (idx == 1) SB_STAMP_AT(kk * 3 + 1, kt * 4 + 0);
                     if constexpr (F8)
                         acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wf[cur][nt], xf[cur][mt], acc[mt][nt],
                                                                                       FMT_W, FMT_X, 0, 0, 0, 0);
@@ -498,30 +462,12 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
                     if (idx < NFRAG && has_next) issue_frag_read(idx, nxt, read_slot, next_kk);
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                SB_STAMP_AT(kk * 3 + 2, kt * 4 + 0);
             }
             ++g;
         };
         const int nkt = cs.ke - cs.kb;
         for (int kt = 0; kt < (next_have ? nkt : nkt - 1); ++kt) k_tile(kt, std::false_type());
         if (!next_have) k_tile(nkt - 1, std::true_type());
-
-        SB_STAMP(201);
-#ifdef SB_GEMM_TIMELINE
-        const bool dbg_round = (unsigned)(round - p.dbg_round0) < 2u;
-        if (dbg_round && lane == 0)
-            *reinterpret_cast<unsigned *>(smem + S * C::STAGE_BYTES + wave * C::EPI_WAVE_BYTES + 203 * 4) =
-                (unsigned)wall_clock64();
-        if (dbg_round && p.dbg && lane < 52 && (blockIdx.x == 0 || blockIdx.x == 37)) {
-            const unsigned *src =
-                reinterpret_cast<const unsigned *>(smem + S * C::STAGE_BYTES + wave * C::EPI_WAVE_BYTES);
-            unsigned *dst = p.dbg + (((blockIdx.x ? 1 : 0) * 8 + wave) * 2 + (round - p.dbg_round0)) * 208;
-            for (int i = lane; i < 208; i += 52)
-                dst[i] = i == 204 ? dbg_epi_end : i == 205 ? dbg_prologue_issued
-                         : (i >= 190 && i < 198) ? dbg_epi[i - 190] : src[i];
-        }
-        dbg_prologue_issued = (unsigned)__builtin_readcyclecounter();
-#endif
         const int m_base = tm * C::BM + wm0, n_base = tn * C::BN + wn0;
         const bool interior = (tm + 1) * C::BM <= p.M && (tn + 1) * C::BN <= p.N;
 
@@ -580,10 +526,8 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
                     *reinterpret_cast<v4bf *>(epi + frow * (C::WTN * 2) + piece * 16 + fhalf * 8) = packed[i];
                 }
             };
-            SB_EPI_STAMP(0);
             convert_block(0);
             write_patch();
-            SB_EPI_STAMP(1);
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
                 v4u val[C::STORES_PER_BLOCK];
@@ -617,7 +561,6 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
                     }
                 }
                 if (mt + 1 < MT) write_patch();
-                SB_EPI_STAMP(2 + mt);
             }
             // Count the stores only where every one of them is certain to have been issued: an overcount would
             // loosen later waits, an undercount merely makes them stricter.
@@ -652,9 +595,6 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
             }
         }
         }
-#ifdef SB_GEMM_TIMELINE
-        dbg_epi_end = (unsigned)__builtin_readcyclecounter();
-#endif
         cs = ns;
         have = next_have;
     }

@@ -112,6 +112,28 @@ def _ptr(t):
     return ctypes.c_void_p(t.data_ptr() if t is not None else None)
 
 
+def _out(t, shape, dtype, device, name):
+    """A fresh output tensor, or the caller's after checking that it has exactly the shape the kernels will write."""
+    if t is None:
+        return torch.empty(tuple(shape), dtype=dtype, device=device)
+    if tuple(t.shape) != tuple(shape) or t.dtype != dtype:
+        raise SwitchBackError("%s must be a %s tensor of shape %s, got %s %s"
+                              % (name, dtype, tuple(shape), t.dtype, tuple(t.shape)))
+    return t
+
+
+def _check_bufs(bufs, b, n, m):
+    """The layer buffers were allocated for one (b, n, m); the kernels write b*n, b*m and m*n codes into them."""
+    if (bufs.b, bufs.n, bufs.m) != (b, n, m):
+        raise SwitchBackError("layer buffers were allocated for (b, n, m) = %s, the call has %s"
+                              % ((bufs.b, bufs.n, bufs.m), (b, n, m)))
+
+
+def _check_ws(ws, need, name="workspace"):
+    if ws.numel() * ws.element_size() < need:
+        raise SwitchBackError("%s holds %d bytes, the call needs %d" % (name, ws.numel() * ws.element_size(), need))
+
+
 def workspace_bytes(op, b, n, m):
     return int(load_library().switchback_workspace_bytes(op, b, n, m))
 
@@ -124,10 +146,10 @@ def _workspace(op, b, n, m, device):
 def quantize_rowwise(x, q=None, state=None):
     """Q_row(x), state_row(x) for a bf16 [rows, cols] tensor -> (int8 [rows, cols], f32 [rows])."""
     lib = load_library()
-    xp = _dev(x, torch.bfloat16, 2)
     rows, cols = x.shape
-    q = torch.empty((rows, cols), dtype=torch.int8, device=x.device) if q is None else q
-    state = torch.empty(rows, dtype=torch.float32, device=x.device) if state is None else state
+    q = _out(q, (rows, cols), torch.int8, x.device, "q")
+    state = _out(state, (rows,), torch.float32, x.device, "state")
+    xp = _dev(x, torch.bfloat16, 2)
     _check(lib.switchback_quantize_rowwise(xp, rows, cols, _dev(q, torch.int8), _dev(state, torch.float32),
                                            _stream()))
     return q, state
@@ -137,7 +159,8 @@ def dequantize_rowwise(q, state, out=None):
     """Row-wise dequantization of SwitchBackM: bf16 [rows, cols] = q * state / 127."""
     lib = load_library()
     rows, cols = q.shape
-    out = torch.empty((rows, cols), dtype=torch.bfloat16, device=q.device) if out is None else out
+    out = _out(out, (rows, cols), torch.bfloat16, q.device, "out")
+    _out(state, (rows,), torch.float32, q.device, "state")
     _check(lib.switchback_dequantize_rowwise(_dev(q, torch.int8, 2), _dev(state, torch.float32), rows, cols,
                                              _dev(out, torch.bfloat16, 2), _stream()))
     return out
@@ -146,12 +169,12 @@ def dequantize_rowwise(q, state, out=None):
 def quantize_tensorwise(w, q=None, q_t=None, state=None, ws=None, transpose=True):
     """Q_tensor(w), Q_tensor(w)^T, state_tensor(w) for a bf16 [rows, cols] tensor."""
     lib = load_library()
-    wp = _dev(w, torch.bfloat16, 2)
     rows, cols = w.shape
-    q = torch.empty((rows, cols), dtype=torch.int8, device=w.device) if q is None else q
-    if transpose and q_t is None:
-        q_t = torch.empty((cols, rows), dtype=torch.int8, device=w.device)
-    state = torch.empty(1, dtype=torch.float32, device=w.device) if state is None else state
+    q = _out(q, (rows, cols), torch.int8, w.device, "q")
+    if transpose or q_t is not None:
+        q_t = _out(q_t, (cols, rows), torch.int8, w.device, "q_t")
+    state = _out(state, (1,), torch.float32, w.device, "state")
+    wp = _dev(w, torch.bfloat16, 2)
     ws = _workspace(SB_OP_QUANTIZE_TENSORWISE, 0, cols, rows, w.device) if ws is None else ws
     _check(lib.switchback_quantize_tensorwise(wp, rows, cols, _dev(q, torch.int8),
                                               _dev(q_t, torch.int8) if q_t is not None else None,
@@ -167,7 +190,9 @@ def matmul_int8_dequant(aq, state_row, bq, state_tensor, out_dtype=torch.bfloat1
     N = bq.shape[0]
     if bq.shape[1] != K:
         raise SwitchBackError("contraction lengths differ")
-    out = torch.empty((M, N), dtype=out_dtype, device=aq.device) if out is None else out
+    out = _out(out, (M, N), out_dtype, aq.device, "out")
+    if state_row is not None:
+        _out(state_row, (M,), torch.float32, aq.device, "state_row")
     _check(lib.switchback_matmul_int8_dequant(
         _dev(aq, torch.int8, 2), _dev(state_row, torch.float32) if state_row is not None else None,
         _dev(bq, torch.int8, 2), _dev(state_tensor, torch.float32) if state_tensor is not None else None,
@@ -199,7 +224,8 @@ def forward(x, w, bufs=None, y=None, y_dtype=torch.bfloat16):
     if w.shape[1] != n:
         raise SwitchBackError("x [b,n] and w [m,n] disagree on n")
     bufs = LayerBuffers(b, n, m, x.device) if bufs is None else bufs
-    y = torch.empty((b, m), dtype=y_dtype, device=x.device) if y is None else y
+    _check_bufs(bufs, b, n, m)
+    y = _out(y, (b, m), y_dtype, x.device, "y")
     _check(lib.switchback_forward(_dev(x, torch.bfloat16, 2), _dev(w, torch.bfloat16, 2), b, n, m,
                                   _dev(y, y_dtype, 2), _SB_DTYPE[y_dtype], ctypes.byref(bufs.saved),
                                   _ptr(bufs.ws_fwd), bufs.ws_fwd.numel(), _stream()))
@@ -211,7 +237,8 @@ def backward_input(dy, bufs, dx=None, dx_dtype=torch.bfloat16):
     lib = load_library()
     b, m = dy.shape
     n = bufs.n
-    dx = torch.empty((b, n), dtype=dx_dtype, device=dy.device) if dx is None else dx
+    _check_bufs(bufs, b, n, m)
+    dx = _out(dx, (b, n), dx_dtype, dy.device, "dx")
     _check(lib.switchback_backward_input(_dev(dy, torch.bfloat16, 2), ctypes.byref(bufs.saved), b, n, m,
                                          _dev(dx, dx_dtype, 2), _SB_DTYPE[dx_dtype], _ptr(bufs.gq),
                                          _ptr(bufs.state_g), _stream()))
@@ -225,8 +252,10 @@ def backward_weight(dy, x, bufs=None, dw=None, dw_dtype=torch.bfloat16):
     n = x.shape[1]
     if x.shape[0] != b:
         raise SwitchBackError("dy [b,m] and x [b,n] disagree on b")
+    if bufs is not None:
+        _check_bufs(bufs, b, n, m)
     ws = bufs.ws_dw if bufs is not None else _workspace(SB_OP_BACKWARD_WEIGHT, b, n, m, dy.device)
-    dw = torch.empty((m, n), dtype=dw_dtype, device=dy.device) if dw is None else dw
+    dw = _out(dw, (m, n), dw_dtype, dy.device, "dw")
     _check(lib.switchback_backward_weight(_dev(dy, torch.bfloat16, 2), _dev(x, torch.bfloat16, 2), b, n, m,
                                           _dev(dw, dw_dtype, 2), _SB_DTYPE[dw_dtype], _ptr(ws), ws.numel(),
                                           _stream()))
@@ -239,8 +268,9 @@ def backward_weight_m(dy, bufs, x_hat=None, dw=None, dw_dtype=torch.bfloat16):
     lib = load_library()
     b, m = dy.shape
     n = bufs.n
-    x_hat = torch.empty((b, n), dtype=torch.bfloat16, device=dy.device) if x_hat is None else x_hat
-    dw = torch.empty((m, n), dtype=dw_dtype, device=dy.device) if dw is None else dw
+    _check_bufs(bufs, b, n, m)
+    x_hat = _out(x_hat, (b, n), torch.bfloat16, dy.device, "x_hat")
+    dw = _out(dw, (m, n), dw_dtype, dy.device, "dw")
     _check(lib.switchback_backward_weight_m(_dev(dy, torch.bfloat16, 2), ctypes.byref(bufs.saved), b, n, m,
                                             _dev(x_hat, torch.bfloat16, 2), _dev(dw, dw_dtype, 2),
                                             _SB_DTYPE[dw_dtype], _ptr(bufs.ws_dw), bufs.ws_dw.numel(), _stream()))
@@ -253,8 +283,8 @@ def quantize_colwise_transpose(w, q_t=None, state=None, ws=None):
     """One absmax per column of w [rows, cols]; returns (q_t int8 [cols, rows], state f32 [cols])."""
     lib = load_library()
     rows, cols = w.shape
-    q_t = torch.empty((cols, rows), dtype=torch.int8, device=w.device) if q_t is None else q_t
-    state = torch.empty(cols, dtype=torch.float32, device=w.device) if state is None else state
+    q_t = _out(q_t, (cols, rows), torch.int8, w.device, "q_t")
+    state = _out(state, (cols,), torch.float32, w.device, "state")
     ws = _workspace(SB_OP_QUANTIZE_COLWISE, 0, cols, rows, w.device) if ws is None else ws
     _check(lib.switchback_quantize_colwise_transpose(_dev(w, torch.bfloat16, 2), rows, cols, _dev(q_t, torch.int8, 2),
                                                      _dev(state, torch.float32), _ptr(ws), ws.numel(), _stream()))
@@ -268,7 +298,9 @@ def matmul_int8_dequant_rc(aq, state_a, bq, state_b, out_dtype=torch.bfloat16, o
     N = bq.shape[0]
     if bq.shape[1] != K:
         raise SwitchBackError("contraction lengths differ")
-    out = torch.empty((M, N), dtype=out_dtype, device=aq.device) if out is None else out
+    out = _out(out, (M, N), out_dtype, aq.device, "out")
+    _out(state_a, (M,), torch.float32, aq.device, "state_a")
+    _out(state_b, (N,), torch.float32, aq.device, "state_b")
     _check(lib.switchback_matmul_int8_dequant_rc(_dev(aq, torch.int8, 2), _dev(state_a, torch.float32),
                                                  _dev(bq, torch.int8, 2), _dev(state_b, torch.float32), M, N, K,
                                                  _dev(out, out_dtype, 2), _SB_DTYPE[out_dtype], _stream()))
@@ -296,7 +328,8 @@ def forward_q(x, w, bufs=None, y=None, y_dtype=torch.bfloat16):
     if w.shape[1] != n:
         raise SwitchBackError("x [b,n] and w [m,n] disagree on n")
     bufs = LayerBuffersQ(b, n, m, x.device) if bufs is None else bufs
-    y = torch.empty((b, m), dtype=y_dtype, device=x.device) if y is None else y
+    _check_bufs(bufs, b, n, m)
+    y = _out(y, (b, m), y_dtype, x.device, "y")
     _check(lib.switchback_forward_q(_dev(x, torch.bfloat16, 2), _dev(w, torch.bfloat16, 2), b, n, m,
                                     _dev(y, y_dtype, 2), _SB_DTYPE[y_dtype], _ptr(bufs.xq), _ptr(bufs.state_x),
                                     _ptr(bufs.wq), _ptr(bufs.state_w_row), _stream()))
@@ -308,7 +341,10 @@ def backward_input_q(dy, w, bufs, dx=None, dx_dtype=torch.bfloat16):
     lib = load_library()
     b, m = dy.shape
     n = w.shape[1]
-    dx = torch.empty((b, n), dtype=dx_dtype, device=dy.device) if dx is None else dx
+    if w.shape[0] != m:
+        raise SwitchBackError("dy [b,m] and w [m,n] disagree on m")
+    _check_bufs(bufs, b, n, m)
+    dx = _out(dx, (b, n), dx_dtype, dy.device, "dx")
     _check(lib.switchback_backward_input_q(_dev(dy, torch.bfloat16, 2), _dev(w, torch.bfloat16, 2), b, n, m,
                                            _dev(dx, dx_dtype, 2), _SB_DTYPE[dx_dtype], _ptr(bufs.gq),
                                            _ptr(bufs.state_g), _ptr(bufs.wq_t), _ptr(bufs.state_w_col),
@@ -339,21 +375,21 @@ def stable_adamw_step(theta, v, u, grad, alpha, beta1, beta2, eps, lam, t, rms_o
 
 def quantize_rowwise_f8(x, fmt, codes=None, state=None):
     lib = load_library()
-    xp = _dev(x, torch.bfloat16, 2)
     rows, cols = x.shape
-    codes = torch.empty((rows, cols), dtype=torch.uint8, device=x.device) if codes is None else codes
-    state = torch.empty(rows, dtype=torch.float32, device=x.device) if state is None else state
+    codes = _out(codes, (rows, cols), torch.uint8, x.device, "codes")
+    state = _out(state, (rows,), torch.float32, x.device, "state")
+    xp = _dev(x, torch.bfloat16, 2)
     _check(lib.switchback_quantize_rowwise_f8(xp, rows, cols, fmt, _ptr(codes), _ptr(state), _stream()))
     return codes, state
 
 
 def quantize_tensorwise_f8(w, fmt, codes=None, codes_t=None, state=None, ws=None):
     lib = load_library()
-    wp = _dev(w, torch.bfloat16, 2)
     rows, cols = w.shape
-    codes = torch.empty((rows, cols), dtype=torch.uint8, device=w.device) if codes is None else codes
-    codes_t = torch.empty((cols, rows), dtype=torch.uint8, device=w.device) if codes_t is None else codes_t
-    state = torch.empty(1, dtype=torch.float32, device=w.device) if state is None else state
+    codes = _out(codes, (rows, cols), torch.uint8, w.device, "codes")
+    codes_t = _out(codes_t, (cols, rows), torch.uint8, w.device, "codes_t")
+    state = _out(state, (1,), torch.float32, w.device, "state")
+    wp = _dev(w, torch.bfloat16, 2)
     ws = _workspace(SB_OP_QUANTIZE_TENSORWISE, 0, cols, rows, w.device) if ws is None else ws
     _check(lib.switchback_quantize_tensorwise_f8(wp, rows, cols, fmt, _ptr(codes), _ptr(codes_t), _ptr(state),
                                                  _ptr(ws), ws.numel(), _stream()))
@@ -366,7 +402,9 @@ def matmul_f8_dequant(aq, fmt_a, state_row, bq, fmt_b, state_tensor, out=None, o
     N = bq.shape[0]
     if bq.shape[1] != K:
         raise SwitchBackError("aq [M,K] and bq [N,K] disagree on K")
-    out = torch.empty((M, N), dtype=out_dtype, device=aq.device) if out is None else out
+    out = torch.empty((M, N), dtype=out_dtype, device=aq.device) if out is None else _out(out, (M, N), out.dtype,
+                                                                                              aq.device, "out")
+    _out(state_row, (M,), torch.float32, aq.device, "state_row")
     _check(lib.switchback_matmul_f8_dequant(_dev(aq, torch.uint8, 2), fmt_a, _ptr(state_row), _dev(bq, torch.uint8, 2),
                                             fmt_b, _ptr(state_tensor), M, N, K, _dev(out, out.dtype, 2),
                                             _SB_DTYPE[out.dtype], _stream()))
@@ -381,7 +419,8 @@ def forward_f8(x, w, bufs=None, y=None, y_dtype=torch.bfloat16, fmt_x=SB_E4M3, f
     if w.shape[1] != n:
         raise SwitchBackError("x [b,n] and w [m,n] disagree on n")
     bufs = LayerBuffers(b, n, m, x.device) if bufs is None else bufs
-    y = torch.empty((b, m), dtype=y_dtype, device=x.device) if y is None else y
+    _check_bufs(bufs, b, n, m)
+    y = _out(y, (b, m), y_dtype, x.device, "y")
     _check(lib.switchback_forward_f8(_dev(x, torch.bfloat16, 2), _dev(w, torch.bfloat16, 2), b, n, m,
                                      _dev(y, y_dtype, 2), _SB_DTYPE[y_dtype], ctypes.byref(bufs.saved), fmt_x, fmt_w,
                                      _ptr(bufs.ws_fwd), bufs.ws_fwd.numel(), _stream()))
@@ -393,7 +432,8 @@ def backward_input_f8(dy, bufs, dx=None, dx_dtype=torch.bfloat16, fmt_g=SB_E5M2,
     lib = load_library()
     b, m = dy.shape
     n = bufs.n
-    dx = torch.empty((b, n), dtype=dx_dtype, device=dy.device) if dx is None else dx
+    _check_bufs(bufs, b, n, m)
+    dx = _out(dx, (b, n), dx_dtype, dy.device, "dx")
     _check(lib.switchback_backward_input_f8(_dev(dy, torch.bfloat16, 2), ctypes.byref(bufs.saved), b, n, m,
                                             _dev(dx, dx_dtype, 2), _SB_DTYPE[dx_dtype], _ptr(bufs.gq),
                                             _ptr(bufs.state_g), fmt_g, fmt_w, _stream()))

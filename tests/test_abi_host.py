@@ -144,6 +144,49 @@ def test_binding_refuses_cpu_tensors():
         sb.quantize_rowwise(torch.zeros(4, 64, dtype=torch.bfloat16))
 
 
+def test_binding_refuses_buffers_of_another_shape(lib):
+    """Caller-supplied layer buffers and outputs must have exactly the shape the kernels will write: the binding raises
+    before any launch (CPU tensors here, so a call that got past the check would raise on the device test instead, with a
+    different message)."""
+    import torch
+    z = lambda *shape, dt=torch.bfloat16: torch.zeros(shape, dtype=dt)
+    bufs = sb.LayerBuffers(8, 64, 128, "cpu")
+    for call in (lambda: sb.forward(z(16, 64), z(128, 64), bufs=bufs),                   # b differs
+                 lambda: sb.forward(z(8, 64), z(192, 64), bufs=bufs),                    # m differs
+                 lambda: sb.backward_input(z(8, 192), bufs),                             # m differs
+                 lambda: sb.backward_weight(z(16, 128), z(16, 64), bufs),                # b differs
+                 lambda: sb.backward_weight_m(z(8, 64), bufs),                           # m differs
+                 lambda: sb.forward_f8(z(8, 128), z(128, 128), bufs=bufs),               # n differs
+                 lambda: sb.backward_input_f8(z(4, 128), bufs)):                         # b differs
+        with pytest.raises(sb.SwitchBackError, match="allocated for"):
+            call()
+    qbufs = sb.LayerBuffersQ(8, 64, 128, "cpu")
+    with pytest.raises(sb.SwitchBackError, match="allocated for"):
+        sb.forward_q(z(8, 64), z(64, 64), bufs=qbufs)
+    with pytest.raises(sb.SwitchBackError, match="allocated for"):
+        sb.backward_input_q(z(9, 128), z(128, 64), qbufs)
+    for call in (lambda: sb.forward(z(8, 64), z(128, 64), bufs=bufs, y=z(8, 64)),        # y too narrow
+                 lambda: sb.forward(z(8, 64), z(128, 64), bufs=bufs, y=z(8, 128, dt=torch.float32)),   # dtype
+                 lambda: sb.backward_input(z(8, 128), bufs, dx=z(4, 64)),
+                 lambda: sb.backward_weight(z(8, 128), z(8, 64), bufs, dw=z(64, 128)),   # transposed
+                 lambda: sb.backward_weight_m(z(8, 128), bufs, x_hat=z(8, 32)),
+                 lambda: sb.quantize_rowwise(z(8, 64), q=z(8, 32, dt=torch.int8)),
+                 lambda: sb.quantize_rowwise(z(8, 64), state=z(4, dt=torch.float32)),
+                 lambda: sb.quantize_tensorwise(z(64, 32), q_t=z(64, 32, dt=torch.int8)),
+                 lambda: sb.dequantize_rowwise(z(8, 64, dt=torch.int8), z(8, dt=torch.float32), out=z(8, 32)),
+                 lambda: sb.quantize_colwise_transpose(z(64, 32), q_t=z(64, 32, dt=torch.int8)),
+                 lambda: sb.matmul_int8_dequant(z(8, 64, dt=torch.int8), z(8, dt=torch.float32),
+                                                z(64, 64, dt=torch.int8), z(1, dt=torch.float32), out=z(8, 32)),
+                 lambda: sb.matmul_int8_dequant(z(8, 64, dt=torch.int8), z(4, dt=torch.float32),
+                                                z(64, 64, dt=torch.int8), z(1, dt=torch.float32)),
+                 lambda: sb.matmul_int8_dequant_rc(z(8, 64, dt=torch.int8), z(8, dt=torch.float32),
+                                                   z(64, 64, dt=torch.int8), z(32, dt=torch.float32)),
+                 lambda: sb.matmul_f8_dequant(z(8, 128, dt=torch.uint8), 0, z(8, dt=torch.float32),
+                                              z(64, 128, dt=torch.uint8), 0, z(1, dt=torch.float32), out=z(8, 32))):
+        with pytest.raises(sb.SwitchBackError, match="must be a"):
+            call()
+
+
 def test_a_missing_library_is_an_error_not_a_fallback(monkeypatch):
     """The product path has no CPU fallback: without the built library every entry point of the binding raises."""
     monkeypatch.setattr(sb, "_lib", None)

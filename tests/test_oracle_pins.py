@@ -551,6 +551,35 @@ def test_stable_adamw_clips_the_update_when_the_second_moment_is_stale(oracle):
     np.testing.assert_allclose(v2, b1h * v1.astype(np.float64), rtol=1e-6)
 
 
+def test_stable_adamw_weight_decay_uses_the_clipped_rate(oracle):
+    """The last line of the algorithm decays the parameters with eta_t * lambda, eta_t = alpha / max(1, RMS_t), not with
+    alpha * lambda.  With RMS_t > 1 and lambda != 0 the two differ:
+    (i)  zero first moment and a gradient that leaves it zero is impossible (v moves with g), so take beta1 = 0 at t > 1:
+         then v_t = g_t exactly and theta_1 = theta_0 - (alpha/RMS) lambda theta_0 - (alpha/RMS) g / (sqrt(u_t) + eps),
+         every factor of which is formed here in binary64 from the definition;
+    (ii) with g = 0 on half of the coordinates (v = 0 there at beta1 = 0) the step on those is exactly
+         theta_0 (1 - alpha lambda / RMS_t): pure decay, at the clipped rate."""
+    rng = np.random.default_rng(55)
+    n, a, b2, eps, lam, t = 600, 5e-3, 0.99, 1e-6, 0.2, 40
+    th0 = (rng.standard_normal(n) + 3.0).astype(np.float32)       # away from zero, so the decay term is not tiny
+    u0 = (np.full(n, 1e-4) * rng.uniform(0.5, 2.0, n)).astype(np.float32)
+    g = (rng.standard_normal(n) * 0.2).astype(np.float32)        # twenty times the history: RMS_t well above 1
+    g[n // 2:] = 0.0
+    th1, v1, u1, rms = oracle.stable_adamw_step(th0, np.zeros(n, np.float32), u0, g, a, 0.0, b2, eps, lam, t)
+    assert rms > 3.0
+    np.testing.assert_array_equal(v1, g)                         # beta1 = 0: the first moment is the gradient
+    eta = a / rms
+    th0d, gd, u1d = th0.astype(np.float64), g.astype(np.float64), u1.astype(np.float64)
+    want = th0d - eta * lam * th0d - eta * gd / (np.sqrt(u1d) + eps)
+    half_ulp = 0.5 * np.spacing(np.abs(want).astype(np.float32)).astype(np.float64)
+    assert np.all(np.abs(th1 - want) <= half_ulp * 1.01)
+    assert np.all(np.abs(th1[n // 2:] - th0d[n // 2:] * (1.0 - a * lam / rms)) <= half_ulp[n // 2:] * 1.01)
+    # decaying with the unclipped rate is a different result, by far more than the rounding of theta
+    wrong = th0d - a * lam * th0d - eta * gd / (np.sqrt(u1d) + eps)
+    assert np.all(np.abs(wrong - want)[n // 2:] > 100 * half_ulp[n // 2:])
+    assert np.all(np.abs(th1 - wrong)[n // 2:] > 50 * half_ulp[n // 2:])
+
+
 def test_stable_adamw_is_invariant_to_gradient_scale(oracle):
     """Adam's update does not change when every gradient is multiplied by a constant (up to eps): neither may the RMS
     nor the parameters."""

@@ -263,14 +263,13 @@ def test_switchback_q_ragged_shapes(oracle, b, n, m):
     check_layer_q(oracle, d)
 
 
-@pytest.mark.parametrize("config,layer", [("vit_b16", 0), ("vit_b16", 1), ("vit_l14", 1), ("vit_l14", 3), ("vit_h14", 2),
-                                          ("vit_h14", 3), ("outlier", 0)])
+@pytest.mark.parametrize("config,layer", [("vit_b16", 0), ("vit_b16", 1), ("vit_l14", 0), ("vit_l14", 1), ("vit_l14", 2),
+                                          ("vit_l14", 3), ("vit_h14", 0), ("vit_h14", 1), ("vit_h14", 2), ("vit_h14", 3),
+                                          ("outlier", 0), ("outlier", 1)])
 def test_switchback_q_full_size_sampled(oracle, config, layer):
     L = I.CONFIGS[config].layers[layer]
     d = I.make_layer_inputs(config, layer)
-    rng = np.random.default_rng(23)
-    rows = np.unique(np.concatenate([[0, 255, 256, L.b - 257, L.b - 1], rng.integers(0, L.b, 16)]))
-    check_layer_q(oracle, d, rows)
+    check_layer_q(oracle, d, one_row_per_block(L.b, 32, np.random.default_rng(23)))
 
 
 # ---------------------------------------------------------------------------------------------------------------
@@ -360,8 +359,17 @@ def test_results_are_deterministic():
 # products on sampled rows the oracle computes one by one
 # ---------------------------------------------------------------------------------------------------------------
 
-FULL = [("vit_b16", 0), ("vit_b16", 1), ("vit_l14", 1), ("vit_l14", 3), ("vit_h14", 0), ("vit_h14", 1),
-        ("vit_h14", 2), ("vit_h14", 3), ("outlier", 0), ("outlier", 1)]
+FULL = [("vit_b16", 0), ("vit_b16", 1), ("vit_l14", 0), ("vit_l14", 1), ("vit_l14", 2), ("vit_l14", 3), ("vit_h14", 0),
+        ("vit_h14", 1), ("vit_h14", 2), ("vit_h14", 3), ("outlier", 0), ("outlier", 1)]
+
+
+def one_row_per_block(count, block, rng):
+    """One index out of every `block` consecutive ones (each 32-row MFMA block of every tile contributes), plus the
+    first and last rows and the rows on either side of the first and last tile edge."""
+    base = np.arange(0, count, block)
+    pick = np.minimum(base + rng.integers(0, block, base.size), count - 1)
+    edges = [0, 1, 255, 256, count - 257, count - 256, count - 2, count - 1]
+    return np.unique(np.concatenate([pick, [e for e in edges if 0 <= e < count]]))
 
 
 @pytest.mark.parametrize("config,layer", FULL)
@@ -370,9 +378,16 @@ def test_layer_full_size_sampled(oracle, config, layer):
     d = I.make_layer_inputs(config, layer)
     x, w, dy = to_dev(d["x"]), to_dev(d["w"]), to_dev(d["dy"])
     bufs = sb.LayerBuffers(L.b, L.n, L.m, DEV)
-    y32, _ = sb.forward(x, w, bufs=bufs, y_dtype=torch.float32)
-    ybf, _ = sb.forward(x, w, bufs=bufs, y_dtype=torch.bfloat16)
-    dxbf = sb.backward_input(dy, bufs, dx_dtype=torch.bfloat16)
+    rng = np.random.default_rng(17)
+    rows = one_row_per_block(L.b, 32, rng)
+    idx = torch.from_numpy(rows).to(DEV)
+    take = lambda t: host(t[idx])
+    yacc = take(sb.forward(x, w, bufs=bufs, y_dtype=torch.int32)[0])
+    y32 = take(sb.forward(x, w, bufs=bufs, y_dtype=torch.float32)[0])
+    ybf = bits_of(sb.forward(x, w, bufs=bufs, y_dtype=torch.bfloat16)[0][idx])
+    dxacc = take(sb.backward_input(dy, bufs, dx_dtype=torch.int32))
+    dx32 = take(sb.backward_input(dy, bufs, dx_dtype=torch.float32))
+    dxbf = bits_of(sb.backward_input(dy, bufs, dx_dtype=torch.bfloat16)[idx])
     dw32 = sb.backward_weight(dy, x, bufs, dw_dtype=torch.float32)
     torch.cuda.synchronize()
 
@@ -388,19 +403,21 @@ def test_layer_full_size_sampled(oracle, config, layer):
     np.testing.assert_array_equal(host(bufs.state_g).view(np.uint32), sg.view(np.uint32))
     np.testing.assert_array_equal(host(bufs.gq), gq)
 
-    # products: sampled token rows (first, last, tile edges, random)
-    rng = np.random.default_rng(17)
-    rows = np.unique(np.concatenate([[0, 1, 255, 256, L.b - 257, L.b - 256, L.b - 2, L.b - 1],
-                                     rng.integers(0, L.b, 24)]))
-    ref = oracle.dequantize(oracle.matmul_int8(xq[rows], wq), sx[rows], sw)
-    idx = torch.from_numpy(rows).to(DEV)
-    assert np.all(np.abs(host(y32[idx]) - ref) <= ulp(ref))
-    assert_bf16_is_rounding_within_one_ulp(bits_of(ybf[idx]), ref, oracle)
-    ref = oracle.dequantize(oracle.matmul_int8(gq[rows], wq_t), sg[rows], sw)
-    assert_bf16_is_rounding_within_one_ulp(bits_of(dxbf[idx]), ref, oracle)
+    # products: one token row out of every 32-row block of every tile row, all columns; raw accumulators bit-exact,
+    # binary32 within one ulp, bf16 the rounding of such a value
+    acc = oracle.matmul_int8(xq[rows], wq)
+    np.testing.assert_array_equal(yacc, acc)
+    ref = oracle.dequantize(acc, sx[rows], sw)
+    assert np.all(np.abs(y32 - ref) <= ulp(ref))
+    assert_bf16_is_rounding_within_one_ulp(ybf, ref, oracle)
+    acc = oracle.matmul_int8(gq[rows], wq_t)
+    np.testing.assert_array_equal(dxacc, acc)
+    ref = oracle.dequantize(acc, sg[rows], sw)
+    assert np.all(np.abs(dx32 - ref) <= ulp(ref))
+    assert_bf16_is_rounding_within_one_ulp(dxbf, ref, oracle)
 
-    # weight gradient: sampled dW rows (columns of dY), full contraction
-    jrows = np.unique(np.concatenate([[0, 255, 256, L.m - 1], rng.integers(0, L.m, 4)]))
+    # weight gradient: one dW row (column of dY) out of every 32-row block, full contraction, all columns
+    jrows = one_row_per_block(L.m, 32, rng)
     dw_ref = oracle.weight_grad(np.ascontiguousarray(d["dy"][:, jrows]), d["x"])
     rms = float(np.sqrt((dw_ref ** 2).mean()))
     got = host(dw32[torch.from_numpy(jrows).to(DEV)]).astype(np.float64)
@@ -414,6 +431,87 @@ def test_layer_full_size_sampled(oracle, config, layer):
     dwm_ref = oracle.weight_grad(np.ascontiguousarray(d["dy"][:, jrows]), xh)
     got = host(dwm[torch.from_numpy(jrows).to(DEV)]).astype(np.float64)
     assert np.abs(got - dwm_ref).max() <= 1e-2 * float(np.sqrt((dwm_ref ** 2).mean()))
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# whole outputs at sizes where every workgroup of the persistent GEMM grids walks several tiles: the hand-over from
+# one tile's last stage into the next tile's first, with the epilogue's stores in the wave's memory books, is compared
+# with the oracle on EVERY element
+# ---------------------------------------------------------------------------------------------------------------
+
+def check_int8_product_whole(oracle, a, b, srow, sw):
+    """aq [M,K], bq [N,K] int8 (host), srow [M] f32, sw f32 scalar: raw accumulators bit-exact, binary32 within one ulp,
+    bf16 the rounding of such a value, every element."""
+    ad, bd = torch.from_numpy(a).to(DEV), torch.from_numpy(b).to(DEV)
+    srd, swd = torch.from_numpy(srow).to(DEV), torch.tensor([sw], dtype=torch.float32, device=DEV)
+    acc_ref = oracle.matmul_int8(a, b)
+    acc = host(sb.matmul_int8_dequant(ad, None, bd, None, out_dtype=torch.int32))
+    np.testing.assert_array_equal(acc, acc_ref)
+    del acc
+    ref = oracle.dequantize(acc_ref, srow, np.float32(sw))
+    del acc_ref
+    y32 = host(sb.matmul_int8_dequant(ad, srd, bd, swd, out_dtype=torch.float32))
+    assert np.all(np.abs(y32 - ref) <= ulp(ref))
+    del y32
+    ybf = bits_of(sb.matmul_int8_dequant(ad, srd, bd, swd, out_dtype=torch.bfloat16))
+    assert_bf16_is_rounding_within_one_ulp(ybf, ref, oracle)
+
+
+@pytest.mark.parametrize("M,N,K", [(4096, 4608, 128), (4096, 4608, 192), (32896, 1280, 192), (6304, 3072, 768),
+                                   (2000, 9280, 320)])
+def test_int8_product_whole_output_over_several_rounds(oracle, M, N, K):
+    """288 to 645 output tiles on at most 256 workgroups: two to three tiles per workgroup, with both k-step
+    instances (K a multiple of 128, and of 64 only), short and long contractions, ragged M."""
+    rng = np.random.default_rng(M + 3 * N + 7 * K)
+    a = rng.integers(-127, 128, size=(M, K)).astype(np.int8)
+    b = rng.integers(-127, 128, size=(N, K)).astype(np.int8)
+    srow = (rng.random(M) * 4 + 1e-3).astype(np.float32)
+    check_int8_product_whole(oracle, a, b, srow, 0.21875)
+
+
+@pytest.mark.parametrize("layer", [1, 3])
+def test_layer_vit_h14_whole_output(oracle, layer):
+    """ViT-H/14 proj (1280 -> 1280) and fc2 (5120 -> 1280) in the launch configuration the benchmark times: Y and dX
+    compared with the oracle on every element (raw accumulators, binary32, bf16); for proj also the whole dW."""
+    L = I.CONFIGS["vit_h14"].layers[layer]
+    d = I.make_layer_inputs("vit_h14", layer)
+    xq, sx = oracle.quantize_rowwise(d["x"])
+    wq, wq_t, sw = oracle.quantize_tensorwise(d["w"])
+    gq, sg = oracle.quantize_rowwise(d["dy"])
+    # the layer calls, every element of the bf16 outputs and of the codes they are built from
+    x, w, dy = to_dev(d["x"]), to_dev(d["w"]), to_dev(d["dy"])
+    bufs = sb.LayerBuffers(L.b, L.n, L.m, DEV)
+    ybf = bits_of(sb.forward(x, w, bufs=bufs)[0])
+    dxbf = bits_of(sb.backward_input(dy, bufs))
+    np.testing.assert_array_equal(host(bufs.xq), xq)
+    np.testing.assert_array_equal(host(bufs.gq), gq)
+    np.testing.assert_array_equal(host(bufs.wq_t), wq_t)
+    ref = oracle.dequantize(oracle.matmul_int8(xq, wq), sx, sw)
+    assert_bf16_is_rounding_within_one_ulp(ybf, ref, oracle)
+    ref = oracle.dequantize(oracle.matmul_int8(gq, wq_t), sg, sw)
+    assert_bf16_is_rounding_within_one_ulp(dxbf, ref, oracle)
+    del ref, ybf, dxbf, bufs
+    # the same two products through the product call: raw accumulators and binary32 as well
+    check_int8_product_whole(oracle, xq, wq, sx, sw)
+    check_int8_product_whole(oracle, gq, wq_t, sg, sw)
+    if layer == 1:
+        dw32 = host(sb.backward_weight(dy, x, dw_dtype=torch.float32)).astype(np.float64)
+        dw_ref = oracle.weight_grad(d["dy"], d["x"])
+        assert np.abs(dw32 - dw_ref).max() <= 1e-2 * float(np.sqrt((dw_ref ** 2).mean()))
+
+
+@pytest.mark.parametrize("b,n,m", [(256, 4352, 4352), (1500, 2304, 2816), (4000, 1280, 1280)])
+def test_weight_gradient_whole_output_over_several_rounds(oracle, b, n, m):
+    """More work items than workgroups (289 tiles; 99 tiles without and 25 tiles with a split of the token range), so
+    every workgroup of the persistent grid takes a second item: dW compared with the oracle on every element."""
+    rng = np.random.default_rng(b + n + m)
+    dyb, xb = rand_bf16(rng, (b, m), 0.1), rand_bf16(rng, (b, n))
+    dy, x = to_dev(dyb), to_dev(xb)
+    dw32 = host(sb.backward_weight(dy, x, dw_dtype=torch.float32))
+    dwbf = bits_of(sb.backward_weight(dy, x, dw_dtype=torch.bfloat16))
+    dw_ref = oracle.weight_grad(dyb, xb)
+    assert np.abs(dw32.astype(np.float64) - dw_ref).max() <= 1e-2 * float(np.sqrt((dw_ref ** 2).mean()))
+    np.testing.assert_array_equal(dwbf, oracle.round_to_bf16(dw32))
 
 
 # ---------------------------------------------------------------------------------------------------------------
@@ -680,14 +778,13 @@ def test_float8_layer_ragged_shapes(oracle, b, n, m):
     check_layer_f8(oracle, d)
 
 
-@pytest.mark.parametrize("config,layer", [("vit_b16", 0), ("vit_b16", 1), ("vit_l14", 1), ("vit_l14", 3), ("vit_h14", 0),
-                                          ("vit_h14", 2), ("vit_h14", 3), ("outlier", 0), ("outlier", 1)])
+@pytest.mark.parametrize("config,layer", [("vit_b16", 0), ("vit_b16", 1), ("vit_l14", 0), ("vit_l14", 1), ("vit_l14", 2),
+                                          ("vit_l14", 3), ("vit_h14", 0), ("vit_h14", 1), ("vit_h14", 2), ("vit_h14", 3),
+                                          ("outlier", 0), ("outlier", 1)])
 def test_float8_layer_full_size_sampled(oracle, config, layer):
     L = I.CONFIGS[config].layers[layer]
     d = I.make_layer_inputs(config, layer)
-    rng = np.random.default_rng(29)
-    rows = np.unique(np.concatenate([[0, 255, 256, L.b - 257, L.b - 1], rng.integers(0, L.b, 16)]))
-    check_layer_f8(oracle, d, rows)
+    check_layer_f8(oracle, d, one_row_per_block(L.b, 32, np.random.default_rng(29)))
 
 
 def test_float8_layer_is_deterministic_and_rejects_unsupported_widths():
