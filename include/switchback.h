@@ -101,6 +101,21 @@ int switchback_matmul_int8_dequant(const int8_t *aq, const float *state_row, con
 int switchback_forward(const void *x_bf16, const void *w_bf16, int64_t b, int64_t n, int64_t m, void *y,
                        sb_dtype y_dtype, const sb_saved *saved, void *ws, size_t ws_bytes, void *stream);
 
+/* switchback_forward for callers that cannot allocate device memory and have no workspace to pass: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels, same results bit for bit, no
+ * workspace argument: the partial maxima of the tensor-wise quantizer (its only scratch, 4 KiB) live in a
+ * file-scope device array of the library, one copy per GPU, held until the process ends.  The call allocates and
+ * frees nothing (the address of the array on the current device is looked up on the first call made on that device).
+ *   Limit: m * n <= SB_FORWARD_STATIC_MAX_WEIGHTS (2^28 weights, four times the largest layer of the paper's
+ *   workloads; the array holds one partial maximum per workgroup of the first pass, at most 1024, which is sized for
+ *   that); larger layers get SB_UNSUPPORTED_SHAPE and should use switchback_forward with their own workspace.
+ *   All calls on one GPU share that GPU's array: two calls that overlap in time on the same GPU (different streams)
+ *   race on it and may quantize W with the wrong absmax.  Serialize them, or use switchback_forward.  Nothing in the
+ *   array needs clearing between calls.  Other arguments, shapes and errors as switchback_forward. */
+#define SB_FORWARD_STATIC_MAX_WEIGHTS ((int64_t)1 << 28)
+int switchback_forward_static(const void *x_bf16, const void *w_bf16, int64_t b, int64_t n, int64_t m, void *y,
+                              sb_dtype y_dtype, const sb_saved *saved, void *stream);
+
 /* Input gradient of Algorithm 1: dX = dequant(Q_row(dY) Q_tensor(W)), dequantized with the state of the
  * quantized dY and the state of W.  Reads saved->wq_t and saved->state_w; fills gq and state_g.
  *   dy [b,m] bf16 in; dx [b,n] out in dx_dtype; gq [b,m] int8 out; state_g [b] f32 out. */

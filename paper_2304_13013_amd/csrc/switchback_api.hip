@@ -2,9 +2,34 @@
 // (arxiv 2304.13013).  Every step runs in the HIP kernels of this library; nothing here touches tensor data.
 #include "sb_common.h"
 
+#include <atomic>
 #include <cmath>
 
+// Scratch of switchback_forward_static: the partial maxima of the tensor-wise quantizer's first pass, one device copy
+// per GPU, held until the process ends.  In host code this name is only a handle for hipGetSymbolAddress; kernels get
+// the per-device address that call returns.
+static __device__ __align__(256) unsigned int scratch[sb::kTensorwisePartials];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::atomic<unsigned int *> g_scratch_ptr[kMaxDevices];  // zero-initialized; index = HIP device ordinal
+
+// Device address of `scratch` on the current device, resolved once per device.  Two host threads racing to the first
+// call on a device both resolve and store the same address.
+int scratch_of_current_device(unsigned int **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SB_HIP_ERROR;
+    unsigned int *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p == nullptr) {
+        void *addr = nullptr;
+        if (hipGetSymbolAddress(&addr, HIP_SYMBOL(scratch)) != hipSuccess || addr == nullptr) return SB_HIP_ERROR;
+        p = static_cast<unsigned int *>(addr);
+        g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return SB_OK;
+}
 
 constexpr int64_t kMaxIntK = 131072;  // 127^2 * K < 2^31 needs K <= 133143; rounded down to a power of two
 
@@ -97,6 +122,31 @@ int switchback_forward(const void *x_bf16, const void *w_bf16, int64_t b, int64_
     // Y = int8 matmul fused with the dequantization.
     hipError_t e = sb::launch_quantize_tensorwise(w_bf16, m, n, saved->wq, saved->wq_t, saved->state_w,
                                                   static_cast<unsigned int *>(ws), s);
+    if (e != hipSuccess) return SB_HIP_ERROR;
+    if (b == 0) return SB_OK;
+    e = sb::launch_quantize_rowwise(x_bf16, b, n, saved->xq, saved->state_x, s);
+    if (e != hipSuccess) return SB_HIP_ERROR;
+    return from_hip(sb::launch_gemm_i8_dequant(saved->xq, saved->state_x, saved->wq, saved->state_w, nullptr, b, m, n, y,
+                                               y_dtype, s));
+}
+
+int switchback_forward_static(const void *x_bf16, const void *w_bf16, int64_t b, int64_t n, int64_t m, void *y,
+                              sb_dtype y_dtype, const sb_saved *saved, void *stream) {
+    int st = layer_shape_status(b, n, m);
+    if (st != SB_OK) return st;
+    if (m * n > SB_FORWARD_STATIC_MAX_WEIGHTS) return SB_UNSUPPORTED_SHAPE;
+    if (!ok_dtype(y_dtype) || saved == nullptr) return SB_INVALID_ARG;
+    if (!ok_ptr(w_bf16) || !ok_ptr(saved->wq) || !ok_ptr(saved->wq_t) || saved->state_w == nullptr)
+        return SB_INVALID_ARG;
+    if (b > 0 && (!ok_ptr(x_bf16) || !ok_ptr(y) || !ok_ptr(saved->xq) || saved->state_x == nullptr))
+        return SB_INVALID_ARG;
+    unsigned int *partials = nullptr;
+    st = scratch_of_current_device(&partials);
+    if (st != SB_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // The kernel sequence of switchback_forward.  Nothing in the scratch has to start at zero: the first pass writes
+    // every partial maximum the second pass reads.
+    hipError_t e = sb::launch_quantize_tensorwise(w_bf16, m, n, saved->wq, saved->wq_t, saved->state_w, partials, s);
     if (e != hipSuccess) return SB_HIP_ERROR;
     if (b == 0) return SB_OK;
     e = sb::launch_quantize_rowwise(x_bf16, b, n, saved->xq, saved->state_x, s);

@@ -54,6 +54,7 @@ def load_library():
     lib.switchback_quantize_tensorwise.argtypes = [vp, i64, i64, vp, vp, vp, vp, sz, vp]
     lib.switchback_matmul_int8_dequant.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, ci, vp]
     lib.switchback_forward.argtypes = [vp, vp, i64, i64, i64, vp, ci, ctypes.POINTER(SbSaved), vp, sz, vp]
+    lib.switchback_forward_static.argtypes = [vp, vp, i64, i64, i64, vp, ci, ctypes.POINTER(SbSaved), vp]
     lib.switchback_backward_input.argtypes = [vp, ctypes.POINTER(SbSaved), i64, i64, i64, vp, ci, vp, vp, vp]
     lib.switchback_backward_weight.argtypes = [vp, vp, i64, i64, i64, vp, ci, vp, sz, vp]
     lib.switchback_dequantize_rowwise.argtypes = [vp, vp, i64, i64, vp, vp]
@@ -78,7 +79,7 @@ def load_library():
     lib.switchback_status_string.argtypes = [ci]
     lib.switchback_status_string.restype = ctypes.c_char_p
     for name in ("switchback_quantize_rowwise", "switchback_quantize_tensorwise", "switchback_matmul_int8_dequant",
-                 "switchback_forward", "switchback_backward_input", "switchback_backward_weight",
+                 "switchback_forward", "switchback_forward_static", "switchback_backward_input", "switchback_backward_weight",
                  "switchback_dequantize_rowwise", "switchback_backward_weight_m",
                  "switchback_quantize_colwise_transpose", "switchback_matmul_int8_dequant_rc",
                  "switchback_forward_q", "switchback_backward_input_q", "switchback_stable_adamw_step",
@@ -229,6 +230,21 @@ def forward(x, w, bufs=None, y=None, y_dtype=torch.bfloat16):
     _check(lib.switchback_forward(_dev(x, torch.bfloat16, 2), _dev(w, torch.bfloat16, 2), b, n, m,
                                   _dev(y, y_dtype, 2), _SB_DTYPE[y_dtype], ctypes.byref(bufs.saved),
                                   _ptr(bufs.ws_fwd), bufs.ws_fwd.numel(), _stream()))
+    return y, bufs
+
+
+def forward_static(x, w, bufs, y=None, y_dtype=torch.bfloat16):
+    """switchback_forward_static: Algorithm 1 forward without a workspace (the library's own per-GPU scratch array
+    holds the tensor-wise partial maxima); the call itself allocates nothing when bufs and y are given."""
+    lib = load_library()
+    b, n = x.shape
+    m = w.shape[0]
+    if w.shape[1] != n:
+        raise SwitchBackError("x [b,n] and w [m,n] disagree on n")
+    _check_bufs(bufs, b, n, m)
+    y = _out(y, (b, m), y_dtype, x.device, "y")
+    _check(lib.switchback_forward_static(_dev(x, torch.bfloat16, 2), _dev(w, torch.bfloat16, 2), b, n, m,
+                                         _dev(y, y_dtype, 2), _SB_DTYPE[y_dtype], ctypes.byref(bufs.saved), _stream()))
     return y, bufs
 
 
