@@ -260,6 +260,54 @@ def main():
             34.0 * sum(t["L"].m * t["L"].n for t in layers), "bytes", reps)
     del plan, opt_all
 
+    # ---- measured ceilings (outside the timed region): what this GPU sustains for code that does nothing but issue
+    # matrix instructions from registers, on the workload's own operand values (the clock the GPU holds under load
+    # depends on how many operand bits toggle), and for a plain copy.  Launch shape of the product kernels: eight waves
+    # per workgroup, two per SIMD; four workgroups per compute unit in a row so that a launch lasts several ms.
+    def ceiling(kind, a, b_, reps=3):
+        wgs, iters = 4 * torch.cuda.get_device_properties(dev).multi_processor_count, 2000
+        sink = torch.empty(wgs * 8 * 64, dtype=torch.float32, device=dev)
+        sb.ceiling_mfma(kind, a, b_, wgs, 8, iters, sink)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            work, _ = sb.ceiling_mfma(kind, a, b_, wgs, 8, iters, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        return work * reps / e0.elapsed_time(e1) / 1e9
+
+    big = max(layers, key=lambda t: t["L"].n * t["L"].m)
+    sb.forward(big["x"], big["w"], bufs=big["bufs"], y=big["y"])           # int8 codes back into the buffers
+    sb.backward_input(big["dy"], big["bufs"], dx=big["dx"])
+    zeros = torch.zeros(1 << 20, dtype=torch.uint8, device=dev)
+    ceilings = {
+        "mfma_int8_workload_codes": round(ceiling(sb.SB_CEILING_I8, big["bufs"].gq, big["bufs"].wq), 1),
+        "mfma_int8_zero_operands": round(ceiling(sb.SB_CEILING_I8, zeros, zeros), 1),
+        "mfma_bf16_workload_values": round(ceiling(sb.SB_CEILING_BF16, big["dy"], big["x"]), 1),
+        "mfma_bf16_zero_operands": round(ceiling(sb.SB_CEILING_BF16, zeros, zeros), 1),
+    }
+    if big["L"].n % 128 == 0 and big["L"].m % 128 == 0:
+        sb.forward_f8(big["x"], big["w"], bufs=big["bufs"], y=big["y"])
+        ceilings["mfma_float8_workload_codes"] = round(
+            ceiling(sb.SB_CEILING_F8, big["bufs"].xq.view(torch.uint8), big["bufs"].wq.view(torch.uint8)), 1)
+        ceilings["mfma_float8_zero_operands"] = round(ceiling(sb.SB_CEILING_F8, zeros, zeros), 1)
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(3)
+    dst = torch.empty_like(src)
+    sb.ceiling_copy(src, dst)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        sb.ceiling_copy(src, dst)
+    e1.record()
+    torch.cuda.synchronize()
+    ceilings["copy_read_plus_write_GBps"] = round(5 * 2.0 * src.numel() / e0.elapsed_time(e1) / 1e6, 1)
+    ceilings["unit"] = "T(FL)OP/s for the matrix-instruction loops (register-resident, no LDS or memory traffic), GB/s for the copy"
+    del src, dst
+    measured = {"int8": ceilings["mfma_int8_workload_codes"], "bf16": ceilings["mfma_bf16_workload_values"],
+                "f8": ceilings.get("mfma_float8_workload_codes"), "bytes": ceilings["copy_read_plus_write_GBps"]}
+
     kernels = {}
     for name, (ms, work, kind) in ops.items():
         if kind == "bytes":
@@ -268,12 +316,18 @@ def main():
             ach, unit, bound = work / ms / 1e9, "TFLOP/s", "mfma"
             peak = PEAK["bf16_TFLOPs"] if kind == "bf16" else PEAK["int8_TOPs"]  # int8 and float8: 5.0 P(FL)OP/s dense
         kernels[name] = {"ms_per_step": round(ms, 4), "bound": bound, "achieved": round(ach, 1), "peak": peak,
-                         "unit": unit, "frac": round(ach / peak, 4)}
+                         "unit": unit, "frac": round(ach / peak, 4), "measured_peak": measured[kind],
+                         "frac_of_measured": round(ach / measured[kind], 4) if measured[kind] else None}
     in_step = [k for k in kernels if "(" not in k]  # names with a parenthesis are measured beside the step
     dominant = max(in_step, key=lambda k: kernels[k]["ms_per_step"])
     roofline = {"kernel": dominant, "bound": kernels[dominant]["bound"], "achieved": kernels[dominant]["achieved"],
                 "peak": kernels[dominant]["peak"], "unit": kernels[dominant]["unit"],
                 "frac": kernels[dominant]["frac"],
+                "measured_peak": kernels[dominant]["measured_peak"],
+                "frac_of_measured": kernels[dominant]["frac_of_measured"],
+                "measured_peak_is": "the register-resident matrix-instruction loop of this run on the workload's operand "
+                                    "values (see ceilings); the published peak assumes 2.4 GHz, which the GPU does "
+                                    "not hold under this load",
                 "traffic": TRAFFIC_BYTES_PER_LAUNCH_VIT_H14.get(dominant) if args.config == "vit_h14" else None,
                 "traffic_unit": "bytes per launch (mean over this kernel's launches of a step), HBM side, from profiles/"}
     op_sum = sum(kernels[k]["ms_per_step"] for k in in_step)
@@ -352,6 +406,7 @@ def main():
         "per_layer": per_layer,
         "roofline": roofline,
         "kernels": kernels,
+        "ceilings": ceilings,
         "sum_of_kernel_ms": round(op_sum, 4),
         "quantize_share_of_kernel_time": round(quant_ms / op_sum, 4),
         "clocks_under_load": clocks,

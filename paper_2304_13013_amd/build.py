@@ -6,7 +6,8 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libswitchback.so")
-SOURCES = ["quantize.hip", "gemm_i8.hip", "gemm_f8.hip", "gemm_bf16_tn.hip", "stable_adamw.hip", "switchback_api.hip"]
+SOURCES = ["quantize.hip", "gemm_i8.hip", "gemm_f8.hip", "gemm_bf16_tn.hip", "stable_adamw.hip", "switchback_api.hip",
+           "ceilings.hip"]
 
 # -ffp-contract=off: the quantizers and the dequantizing epilogue promise one rounding per operation.
 # The packed-fp32 feature is switched off on purpose (plain v_mul/v_add/v_fma only).

@@ -74,6 +74,10 @@ def load_library():
     lib.switchback_stable_adamw_plan.restype = i64
     lib.switchback_stable_adamw_step_multi.argtypes = [vp, ci, i64, ci, cf, cf, cf, cf, cf, i64, vp, vp, sz, vp]
     lib.switchback_stable_adamw_step_multi.restype = ci
+    lib.switchback_ceiling_mfma.argtypes = [ci, vp, sz, vp, sz, ci, ci, ci, vp, ctypes.POINTER(ctypes.c_double), vp]
+    lib.switchback_ceiling_mfma.restype = ci
+    lib.switchback_ceiling_copy.argtypes = [vp, vp, sz, vp]
+    lib.switchback_ceiling_copy.restype = ci
     lib.switchback_workspace_bytes.argtypes = [ci, i64, i64, i64]
     lib.switchback_workspace_bytes.restype = sz
     lib.switchback_status_string.argtypes = [ci]
@@ -454,6 +458,38 @@ def backward_input_f8(dy, bufs, dx=None, dx_dtype=torch.bfloat16, fmt_g=SB_E5M2,
                                             _dev(dx, dx_dtype, 2), _SB_DTYPE[dx_dtype], _ptr(bufs.gq),
                                             _ptr(bufs.state_g), fmt_g, fmt_w, _stream()))
     return dx
+
+
+# ---- measured ceilings (include/switchback_ceilings.h): measurement aids of the benchmark, not part of the layer -----
+
+SB_CEILING_I8, SB_CEILING_BF16, SB_CEILING_F8 = 0, 1, 2
+
+
+def ceiling_mfma(kind, a_codes, b_codes, workgroups, waves_per_workgroup, iters, sink=None):
+    """Enqueue the register-resident matrix-instruction loop on operand bytes taken from a_codes / b_codes (any dtype,
+    contiguous).  Returns (operations performed, sink)."""
+    lib = load_library()
+    lanes = workgroups * waves_per_workgroup * 64
+    sink = torch.empty(lanes, dtype=torch.float32, device=a_codes.device) if sink is None else sink
+    if sink.numel() < lanes or sink.dtype != torch.float32:
+        raise SwitchBackError("sink must hold one f32 per launched lane")
+    for t in (a_codes, b_codes, sink):
+        if not t.is_cuda or not t.is_contiguous():
+            raise SwitchBackError("tensors must be contiguous and live on the GPU")
+    ops = ctypes.c_double(0.0)
+    _check(lib.switchback_ceiling_mfma(kind, _ptr(a_codes), a_codes.numel() * a_codes.element_size(), _ptr(b_codes),
+                                       b_codes.numel() * b_codes.element_size(), workgroups, waves_per_workgroup,
+                                       iters, _ptr(sink), ctypes.byref(ops), _stream()))
+    return ops.value, sink
+
+
+def ceiling_copy(src, dst):
+    """Enqueue a plain device copy src -> dst (same byte count, a multiple of 16)."""
+    lib = load_library()
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes or not (src.is_cuda and dst.is_cuda):
+        raise SwitchBackError("src and dst must be GPU tensors of the same byte count")
+    _check(lib.switchback_ceiling_copy(_dev(src, src.dtype), _dev(dst, dst.dtype), nbytes, _stream()))
 
 
 class AdamwPlan:

@@ -20,15 +20,22 @@ def lib():
 
 
 def declared_functions():
-    with open(os.path.join(ROOT, "include", "switchback.h")) as fh:
-        text = re.sub(r"/\*.*?\*/", "", fh.read(), flags=re.S)
-    return sorted(set(re.findall(r"\b(switchback_\w+)\s*\(", text)))
+    """Every function any header under include/ declares."""
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    for header in sorted(os.listdir(inc)):
+        if header.endswith(".h"):
+            with open(os.path.join(inc, header)) as fh:
+                text = re.sub(r"/\*.*?\*/", "", fh.read(), flags=re.S)
+            names |= set(re.findall(r"\b(switchback_\w+)\s*\(", text))
+    return sorted(names)
 
 
 def test_exports_every_declared_symbol(lib):
     names = declared_functions()
     assert {"switchback_quantize_rowwise", "switchback_quantize_tensorwise", "switchback_forward",
-            "switchback_backward_input", "switchback_backward_weight"} <= set(names)
+            "switchback_backward_input", "switchback_backward_weight", "switchback_forward_static",
+            "switchback_ceiling_mfma", "switchback_ceiling_copy"} <= set(names)
     for name in names:
         assert hasattr(lib, name), name
 
@@ -136,6 +143,21 @@ def test_bad_arguments_are_rejected_before_launch(lib):
     assert multi(null, 3, 3649, 0, *good, 1, null, fake, 1 << 20, null) == INVALID
     assert multi(fake, 3, 3649, 0, *good, 0, null, fake, 1 << 20, null) == INVALID
     assert multi(null, 0, 0, 0, *good, 1, null, null, 0, null) == 0
+    # the allocation-free forward: shape limits first, then pointers; nothing is launched
+    assert lib.switchback_forward_static(fake, fake, 8, 16384, 16448, fake, 0, sp, null) == SHAPE   # m * n > 2^28
+    assert lib.switchback_forward_static(fake, fake, 8, 100, 64, fake, 0, sp, null) == SHAPE
+    assert lib.switchback_forward_static(null, fake, 8, 64, 64, fake, 0, sp, null) == INVALID
+    assert lib.switchback_forward_static(fake, fake, 8, 64, 64, fake, 9, sp, null) == INVALID
+    # the measurement aids validate their arguments too
+    ceil = lib.switchback_ceiling_mfma
+    assert ceil(0, fake, 1024, fake, 1024, 0, 8, 10, fake, None, null) == INVALID                   # no workgroups
+    assert ceil(0, fake, 1000, fake, 1024, 8, 8, 10, fake, None, null) == INVALID                   # not whole fragments
+    assert ceil(2, fake, 1024, fake, 2048, 8, 8, 10, fake, None, null) == INVALID                   # float8 fragments are 2 KiB
+    assert ceil(3, fake, 1024, fake, 1024, 8, 8, 10, fake, None, null) == INVALID
+    assert ceil(0, fake, 1024, fake, 1024, 8, 5, 10, fake, None, null) == INVALID
+    assert lib.switchback_ceiling_copy(fake, odd, 64, null) == INVALID
+    assert lib.switchback_ceiling_copy(fake, fake, 24, null) == INVALID
+    assert lib.switchback_ceiling_copy(fake, fake, 0, null) == 0
 
 
 def test_binding_refuses_cpu_tensors():
