@@ -13,6 +13,11 @@ typedef GemmI8Cfg<128, 2, 4, 3, 1> K128;
 typedef GemmI8Cfg<64, 4, 8, 4, 1> K64;
 // Row-and-column scales (SwitchBackQ): the 32 column states a lane keeps need the registers of the even split.
 typedef GemmI8Cfg<128, 2, 4, 4, 1> K128Q;
+// Products with few output tiles (ViT-B/16's 768-wide outputs make 75 tiles of 256x256 for 256 compute units):
+// 128x128 tiles, four waves, two workgroups per compute unit.  Twice the operand bytes per multiply-add, so it loses
+// to the large tile as soon as that one fills the GPU (measured: 26 against 33 us at 75 large tiles, 26 against 24 us
+// at 300).
+typedef GemmI8Cfg<128, 2, 4, 2, 1, 128, 128, 2, 2> K128S;
 
 #define SB_GEMM_I8_ENTRY(name, CFG, OUT) \
     __global__ __launch_bounds__(CFG::THREADS) void name(GemmI8Args p) { gemm_i8_dequant_body<CFG, OUT>(p); }
@@ -22,6 +27,15 @@ SB_GEMM_I8_ENTRY(gemm_i8_k128_i32, K128, OUT_I32)
 SB_GEMM_I8_ENTRY(gemm_i8_k64_bf16, K64, OUT_BF16)
 SB_GEMM_I8_ENTRY(gemm_i8_k64_f32, K64, OUT_F32)
 SB_GEMM_I8_ENTRY(gemm_i8_k64_i32, K64, OUT_I32)
+// Two waves per SIMD for the four-wave configuration (two workgroups per compute unit): at most 256 registers per lane.
+#define SB_GEMM_I8_ENTRY_S(name, CFG, OUT)                                                                     \
+    __global__ __launch_bounds__(CFG::THREADS) __attribute__((amdgpu_waves_per_eu(2))) void name(GemmI8Args p) { \
+        gemm_i8_dequant_body<CFG, OUT>(p);                                                                     \
+    }
+SB_GEMM_I8_ENTRY_S(gemm_i8_k128s_bf16, K128S, OUT_BF16)
+SB_GEMM_I8_ENTRY_S(gemm_i8_k128s_f32, K128S, OUT_F32)
+SB_GEMM_I8_ENTRY_S(gemm_i8_k128s_i32, K128S, OUT_I32)
+#undef SB_GEMM_I8_ENTRY_S
 #define SB_GEMM_I8_ENTRY_Q(name, CFG, OUT) \
     __global__ __launch_bounds__(CFG::THREADS) void name(GemmI8Args p) { gemm_i8_dequant_body<CFG, OUT, true>(p); }
 SB_GEMM_I8_ENTRY_Q(gemm_i8q_k128_bf16, K128Q, OUT_BF16)
@@ -40,9 +54,17 @@ hipError_t launch(void (*kernel)(GemmI8Args), std::atomic<bool> *attr_set, GemmI
         attr_set->store(true, std::memory_order_release);
     }
     int grid = 0;
-    gemm_i8_prepare<C>(args, num_compute_units(), &grid);
+    // Workgroups that fit a compute unit at once: its 160 KiB of LDS decide (registers allow two waves per SIMD).
+    constexpr int per_cu = C::LDS_BYTES * 2 <= 160 * 1024 && C::NWAVES == 4 ? 2 : 1;
+    gemm_i8_prepare<C>(args, num_compute_units() * per_cu, &grid);
     kernel<<<grid, C::THREADS, C::LDS_BYTES, stream>>>(args);
     return hipGetLastError();
+}
+
+// Few large tiles: fewer than half as many 256x256 tiles as compute units.
+bool few_tiles(int64_t M, int64_t N) {
+    const int64_t tiles = ((M + 255) / 256) * ((N + 255) / 256);
+    return tiles * 2 <= num_compute_units();
 }
 
 }  // namespace
@@ -76,8 +98,15 @@ hipError_t launch_gemm_i8_dequant(const int8_t *aq, const float *state_row, cons
         return out_dtype == SB_BF16 ? launch<K64>(gemm_i8q_k64_bf16, &q_attr_set[2], args, stream)
                                     : launch<K64>(gemm_i8q_k64_f32, &q_attr_set[3], args, stream);
     }
-    static std::atomic<bool> attr_set[6];  // zero-initialized
+    static std::atomic<bool> attr_set[9];  // zero-initialized
     const bool wide = K % 128 == 0;
+    if (wide && few_tiles(M, N)) {
+        switch (out_dtype) {
+            case SB_BF16: return launch<K128S>(gemm_i8_k128s_bf16, &attr_set[6], args, stream);
+            case SB_F32: return launch<K128S>(gemm_i8_k128s_f32, &attr_set[7], args, stream);
+            default: return launch<K128S>(gemm_i8_k128s_i32, &attr_set[8], args, stream);
+        }
+    }
     switch (out_dtype) {
         case SB_BF16:
             return wide ? launch<K128>(gemm_i8_k128_bf16, &attr_set[0], args, stream)

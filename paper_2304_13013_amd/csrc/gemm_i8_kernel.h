@@ -52,15 +52,22 @@ enum { OUT_BF16 = 0, OUT_F32 = 1, OUT_I32 = 2 };
 // v_mfma_f32_32x32x64_f8f6f4 with binary32 accumulators, scale state_tensor (the codes already lie in [-1, 1]).
 enum { MATH_I8 = 0, MATH_F8 = 4 };
 
-template <int BK_, int STAGES_, int LOADERS_, int MT_LOADER_ = 4, int STORE_NT_ = 0>
+// BM_ x BN_ output tile per workgroup of WAVES_M_ x WAVES_N_ waves; a wave tile is BM_/WAVES_M_ rows by 64 columns.
+// The default is the 256x256 tile of eight waves (two per SIMD, one workgroup per compute unit).  The 128x128 tile of
+// four waves needs 80 KiB of LDS and 256 registers per lane, so two workgroups share a compute unit, one wave of each
+// per SIMD: they drift apart, and the epilogue of one runs under the matrix instructions of the other.  It moves twice
+// the operand bytes per multiply-add, which is why it only serves products with too few 256x256 tiles to fill the GPU.
+template <int BK_, int STAGES_, int LOADERS_, int MT_LOADER_ = 4, int STORE_NT_ = 0, int BM_ = 256, int BN_ = 256,
+          int WAVES_M_ = 2, int WAVES_N_ = 4>
 struct GemmI8Cfg {
     static constexpr int STORE_NT = STORE_NT_;  // 1: non-temporal output stores (the output should not evict operand panels from L2)
-    static constexpr int BM = 256, BN = 256, BK = BK_, STAGES = STAGES_;
-    static constexpr int WAVES_M = 2, WAVES_N = 4, NWAVES = 8, THREADS = NWAVES * 64;
-    static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;  // wave tile 128 x 64
+    static constexpr int BM = BM_, BN = BN_, BK = BK_, STAGES = STAGES_;
+    static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, NWAVES = WAVES_M * WAVES_N, THREADS = NWAVES * 64;
+    static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;  // wave tile: 128 x 64 in the default configuration
     static constexpr int NT = WTN / 32;                           // 32-column MFMA blocks per wave tile
-    static constexpr int MT_LOADER = MT_LOADER_;  // 32-row MFMA blocks of a loader wave's tile; when < 4 its SIMD partner
-                                                  // (wave + 4) takes the other 8 - MT_LOADER blocks of the wave column
+    static constexpr int MT_EVEN = WTM / 32;                      // 32-row MFMA blocks per wave tile when all waves get the same
+    static constexpr int MT_LOADER = MT_LOADER_;  // 32-row MFMA blocks of a loader wave's tile; when < MT_EVEN its SIMD partner
+                                                  // (wave + 4) takes the other 2 * MT_EVEN - MT_LOADER blocks of the wave column
     static constexpr int KK = BK / 32;                            // MFMA k-steps per stage
     static constexpr int CPR = BK / 16;                           // 16-byte chunks per tile row
     static constexpr int RPS = 1024 / BK;                         // tile rows per 1 KiB request
@@ -74,12 +81,16 @@ struct GemmI8Cfg {
     static constexpr int EPI_WAVE_BYTES = 32 * WTN * 2;           // 32 rows of bf16 per wave
     static constexpr int STORES_PER_BLOCK = EPI_WAVE_BYTES / 1024;  // 16-byte global stores per lane per 32-row block
     static constexpr int LDS_BYTES = STAGES * STAGE_BYTES + NWAVES * EPI_WAVE_BYTES;
+    static constexpr int MT_MAX = MT_LOADER < MT_EVEN ? 2 * MT_EVEN - MT_LOADER : MT_EVEN;  // largest wave tile, in blocks
     static_assert(BK == 64 || BK == 128, "BK");
     static_assert(STAGES >= 2 && STAGES <= 4, "STAGES");
-    static_assert(NT == 2 && MT_LOADER >= 2 && MT_LOADER <= 4, "the fragment schedule is written for MT x 2 MFMA blocks per wave");
-    static_assert((LOADERS == 4 || LOADERS == 8) && BM % RPL == 0 && LPW % NVAR == 0, "loader split");
-    static_assert(MT_LOADER == 4 || LOADERS == 4, "an uneven split pairs a loader wave with a non-loading one");
-    static_assert(LPW * (STAGES - 1) + MT_LOADER * STORES_PER_BLOCK + MT_LOADER < 64, "vmcnt range");
+    static_assert(BM % (32 * WAVES_M) == 0 && (NWAVES == 4 || NWAVES == 8), "wave grid");
+    static_assert(NT == 2 && MT_LOADER >= 2 && MT_LOADER <= MT_EVEN && MT_EVEN <= 4,
+                  "the fragment schedule is written for MT x 2 MFMA blocks per wave");
+    static_assert((LOADERS == 4 || LOADERS == 8) && LOADERS <= NWAVES && BM % RPL == 0 && LPW % NVAR == 0, "loader split");
+    static_assert(MT_LOADER == MT_EVEN || (LOADERS == 4 && NWAVES == 8 && WAVES_M == 2),
+                  "an uneven split pairs a loader wave with the non-loading wave below it in the same wave column");
+    static_assert(LPW * (STAGES - 1) + MT_MAX * STORES_PER_BLOCK + MT_MAX < 64, "vmcnt range");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS");
 };
 
@@ -605,12 +616,12 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
 template <class C, int OUT, bool COLSCALE = false, int MATH = MATH_I8>
 __device__ __forceinline__ void gemm_i8_dequant_body(const GemmI8Args &p) {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform: what derives from it is scalar
-    if (C::MT_LOADER == 4)
-        gemm_i8_dequant_role<C, OUT, 4, COLSCALE, MATH>(p, wave, (wave / C::WAVES_N) * C::WTM);
+    if (C::MT_LOADER == C::MT_EVEN)
+        gemm_i8_dequant_role<C, OUT, C::MT_EVEN, COLSCALE, MATH>(p, wave, (wave / C::WAVES_N) * C::WTM);
     else if (wave < C::LOADERS)
         gemm_i8_dequant_role<C, OUT, C::MT_LOADER, COLSCALE, MATH>(p, wave, 0);
     else
-        gemm_i8_dequant_role<C, OUT, 8 - C::MT_LOADER, COLSCALE, MATH>(p, wave, C::MT_LOADER * 32);
+        gemm_i8_dequant_role<C, OUT, 2 * C::MT_EVEN - C::MT_LOADER, COLSCALE, MATH>(p, wave, C::MT_LOADER * 32);
 }
 
 // Launch geometry shared by the entry points: a persistent grid, a multiple of the XCD count, at most one workgroup
