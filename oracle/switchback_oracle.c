@@ -179,6 +179,30 @@ void sbo_dequantize_rowcol(const int32_t *acc, int64_t M, int64_t N, const float
         }
 }
 
+/* The linear layer's bias and the layer-scale of the transformer block, applied to a dequantized product (the
+ * block equations of the paper's section on feature magnitudes: x' = x + gamma * block(x), where block ends in a
+ * linear layer, i.e. gamma_j * (y_ij + bias_j); SwitchBackLinear is an nn.Linear and has a bias, Algorithm 1 leaves
+ * it out).  One binary32 rounding per operation, in this order: z = fl(y + bias[j]) if bias is given, then
+ * fl(gamma[j] * z) if gamma is given.  y [M,N] f32 in; bias, gamma [N] f32 or NULL; out [M,N] f32;
+ * out64 (may be NULL): gamma[j] * (y64[i,j] + bias[j]) in binary64 from the binary64 product y64. */
+void sbo_bias_layerscale(const float *y, const double *y64, int64_t M, int64_t N, const float *bias,
+                         const float *gamma, float *out, double *out64) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M; ++i)
+        for (int64_t j = 0; j < N; ++j) {
+            float z = y[i * N + j];
+            if (bias) z = z + bias[j];
+            if (gamma) z = gamma[j] * z;
+            out[i * N + j] = z;
+            if (out64) {
+                double w = y64[i * N + j];
+                if (bias) w = w + (double)bias[j];
+                if (gamma) w = (double)gamma[j] * w;
+                out64[i * N + j] = w;
+            }
+        }
+}
+
 void sbo_round_to_bf16(const float *y, int64_t count, uint16_t *out) {
     for (int64_t e = 0; e < count; ++e) out[e] = f32_to_bf16_rne(y[e]);
 }

@@ -118,6 +118,25 @@ def dequantize(acc, state_row, state_tensor, want_f64=False):
     return (y32, y64) if want_f64 else y32
 
 
+def bias_layerscale(y32, bias=None, gamma=None, y64=None):
+    """out[i,j] = gamma[j] * (y[i,j] + bias[j]) in binary32, one rounding per operation, bias first (either vector may
+    be None).  With y64 (the binary64 product) also returns the same expression in binary64."""
+    y32 = np.ascontiguousarray(y32, dtype=np.float32)
+    M, N = y32.shape
+    vec = lambda v: None if v is None else np.ascontiguousarray(v, dtype=np.float32)
+    bias, gamma = vec(bias), vec(gamma)
+    assert (bias is None or bias.shape == (N,)) and (gamma is None or gamma.shape == (N,))
+    out = np.empty((M, N), np.float32)
+    out64 = None
+    if y64 is not None:
+        y64 = np.ascontiguousarray(y64, dtype=np.float64)
+        out64 = np.empty((M, N), np.float64)
+    _load().sbo_bias_layerscale(_p(y32), _p(y64) if y64 is not None else None, _i64(M), _i64(N),
+                                _p(bias) if bias is not None else None, _p(gamma) if gamma is not None else None,
+                                _p(out), _p(out64) if out64 is not None else None)
+    return (out, out64) if y64 is not None else out
+
+
 def dequantize_rowcol(acc, state_row, state_col, want_f64=False):
     """SwitchBackQ dequantization: y = acc * state_row[i] * state_col[j] / 127^2 (binary32, column constant first)."""
     acc = np.ascontiguousarray(acc, dtype=np.int32)

@@ -479,6 +479,53 @@ def test_switchback_q_layer_bounds(oracle):
 
 
 # ---------------------------------------------------------------------------------------------------------------
+# bias and layer-scale on the dequantized product (gamma * (X W^T + bias): the block equations with layer-scale)
+# ---------------------------------------------------------------------------------------------------------------
+
+def test_bias_and_layerscale_special_cases(oracle):
+    """What the definition fixes without any arithmetic of its own: no vectors = identity; gamma = 0 (the paper's
+    zero initialisation) gives an exactly zero block output whatever the bias; gamma = 1 and bias = 0 change nothing;
+    a zero product row returns gamma * bias; powers of two in gamma scale exactly; gamma = -1 flips signs."""
+    rng = np.random.default_rng(61)
+    M, N, K = 24, 40, 64
+    acc = oracle.matmul_int8(rng.integers(-127, 128, (M, K)).astype(np.int8), rng.integers(-127, 128, (N, K)).astype(np.int8))
+    srow = rng.uniform(0.5, 3.0, M).astype(np.float32)
+    srow[3] = 0.0                                                  # an all-zero token: zero product row
+    y = oracle.dequantize(acc, srow, np.float32(0.37))
+    bias = rng.standard_normal(N).astype(np.float32)
+    gamma = rng.standard_normal(N).astype(np.float32)
+    np.testing.assert_array_equal(oracle.bias_layerscale(y), y)
+    assert not oracle.bias_layerscale(y, bias, np.zeros(N, np.float32)).any()
+    np.testing.assert_array_equal(oracle.bias_layerscale(y, np.zeros(N, np.float32), np.ones(N, np.float32)), y)
+    out = oracle.bias_layerscale(y, bias, gamma)
+    np.testing.assert_array_equal(out[3], gamma * bias)            # one correctly rounded product per element
+    np.testing.assert_array_equal(oracle.bias_layerscale(y, bias, None)[3], bias)
+    np.testing.assert_array_equal(oracle.bias_layerscale(y, bias, gamma * np.float32(2.0 ** -7)), out * np.float32(2.0 ** -7))
+    np.testing.assert_array_equal(oracle.bias_layerscale(y, bias, -np.ones(N, np.float32)), -oracle.bias_layerscale(y, bias))
+
+
+def test_bias_and_layerscale_order_and_accuracy(oracle):
+    """(i) The binary32 result equals NumPy's own binary32 evaluation of gamma * (y + bias) (an IEEE add, then an IEEE
+    multiply: the library routine this reduces to), and differs from the other order gamma * y + gamma * bias on some
+    elements, so the order is pinned.  (ii) Against the binary64 expression on the binary64 product: each of the two
+    operations adds half an ulp of its own result, on top of the product's two ulps carried through."""
+    rng = np.random.default_rng(62)
+    M, N, K = 64, 96, 256
+    acc = oracle.matmul_int8(rng.integers(-127, 128, (M, K)).astype(np.int8), rng.integers(-127, 128, (N, K)).astype(np.int8))
+    srow = rng.uniform(0.5, 3.0, M).astype(np.float32)
+    y, y64 = oracle.dequantize(acc, srow, np.float32(0.0123), want_f64=True)
+    bias = (rng.standard_normal(N) * 5).astype(np.float32)
+    gamma = rng.standard_normal(N).astype(np.float32)
+    out, out64 = oracle.bias_layerscale(y, bias, gamma, y64=y64)
+    np.testing.assert_array_equal(out, gamma[None, :] * (y + bias[None, :]))
+    assert (out != gamma[None, :] * y + gamma[None, :] * bias[None, :]).any()
+    np.testing.assert_array_equal(out64, gamma.astype(np.float64)[None, :] * (y64 + bias.astype(np.float64)[None, :]))
+    u = lambda v: np.spacing(np.abs(v).astype(np.float32)).astype(np.float64)
+    bound = np.abs(gamma.astype(np.float64))[None, :] * (2 * u(y) + 0.5 * u(y + bias[None, :])) + 0.5 * u(out) + 1e-300
+    assert np.all(np.abs(out.astype(np.float64) - out64) <= bound)
+
+
+# ---------------------------------------------------------------------------------------------------------------
 # StableAdamW (the optimizer algorithm: AdamW + update clipping by max(1, RMS_t))
 # ---------------------------------------------------------------------------------------------------------------
 
