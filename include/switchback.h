@@ -169,6 +169,25 @@ int switchback_backward_input_q(const void *dy_bf16, const void *w_bf16, int64_t
                                 sb_dtype dx_dtype, int8_t *gq, float *state_g, int8_t *wq_t, float *state_w_col,
                                 void *ws, size_t ws_bytes, void *stream);
 
+/* The linear layer's bias and the transformer block's layer-scale, fused into the epilogue of the int8 product (the
+ * block equations of the section on feature magnitudes: x' = x + gamma * block(x), where block ends in a linear layer,
+ * so the product's output is gamma[j] * (y[i,j] + bias[j]); the paper initialises gamma with zeros.  SwitchBackLinear
+ * is an nn.Linear and has a bias; Algorithm 1 leaves it out, which is what the calls above compute).  With y the
+ * dequantized product of switchback_matmul_int8_dequant, in binary32 with one rounding per operation:
+ *     z = y + bias[j]   (skipped when bias is NULL),    out = gamma[j] * z   (skipped when gamma is NULL),
+ * then rounded to nearest-even when out_dtype is SB_BF16.  bias, gamma: [N] f32 device vectors (16-byte aligned) or
+ * NULL; out_dtype SB_BF16 or SB_F32; shapes as switchback_matmul_int8_dequant / switchback_forward.  The backward pass
+ * of the two elementwise operations (dY scaled by gamma before the calls of Algorithm 1's backward, the two vector
+ * gradients) is the caller's.
+ *   switchback_forward_bias_layerscale: switchback_forward (fills `saved` the same way) with this epilogue. */
+int switchback_matmul_int8_dequant_bias_layerscale(const int8_t *aq, const float *state_row, const int8_t *bq,
+                                                   const float *state_tensor, const float *bias, const float *gamma,
+                                                   int64_t M, int64_t N, int64_t K, void *out, sb_dtype out_dtype,
+                                                   void *stream);
+int switchback_forward_bias_layerscale(const void *x_bf16, const void *w_bf16, const float *bias, const float *gamma,
+                                       int64_t b, int64_t n, int64_t m, void *y, sb_dtype y_dtype,
+                                       const sb_saved *saved, void *ws, size_t ws_bytes, void *stream);
+
 /* The float8 variant of the layer (the "float8" paragraph of Section 2.2.1: the same code path with
  * round(127 x / absmax(x)) replaced by float8cast(x / absmax(x)); the paper simulates it in 16 bit, here the codes are
  * real 8-bit floats and the product runs on the float8 matrix instructions).  Formats are those of the format paper the

@@ -44,6 +44,18 @@ SB_GEMM_I8_ENTRY_Q(gemm_i8q_k64_bf16, K64, OUT_BF16)
 SB_GEMM_I8_ENTRY_Q(gemm_i8q_k64_f32, K64, OUT_F32)
 #undef SB_GEMM_I8_ENTRY_Q
 #undef SB_GEMM_I8_ENTRY
+// Bias and layer-scale after the dequantization: the even wave split (the two vectors take 64 registers in the epilogue).
+#define SB_GEMM_I8_ENTRY_P(name, CFG, OUT)                                                                     \
+    __global__ __launch_bounds__(CFG::THREADS) __attribute__((amdgpu_waves_per_eu(2))) void name(GemmI8Args p) { \
+        gemm_i8_dequant_body<CFG, OUT, false, MATH_I8, true>(p);                                               \
+    }
+SB_GEMM_I8_ENTRY_P(gemm_i8p_k128_bf16, K128Q, OUT_BF16)
+SB_GEMM_I8_ENTRY_P(gemm_i8p_k128_f32, K128Q, OUT_F32)
+SB_GEMM_I8_ENTRY_P(gemm_i8p_k64_bf16, K64, OUT_BF16)
+SB_GEMM_I8_ENTRY_P(gemm_i8p_k64_f32, K64, OUT_F32)
+SB_GEMM_I8_ENTRY_P(gemm_i8p_k128s_bf16, K128S, OUT_BF16)
+SB_GEMM_I8_ENTRY_P(gemm_i8p_k128s_f32, K128S, OUT_F32)
+#undef SB_GEMM_I8_ENTRY_P
 
 template <class C>
 hipError_t launch(void (*kernel)(GemmI8Args), std::atomic<bool> *attr_set, GemmI8Args args, hipStream_t stream) {
@@ -83,6 +95,23 @@ int num_compute_units() {
         cached.store(n, std::memory_order_relaxed);
     }
     return n;
+}
+
+hipError_t launch_gemm_i8_dequant_post(const int8_t *aq, const float *state_row, const int8_t *bq,
+                                       const float *state_tensor, const float *bias, const float *gamma, int64_t M,
+                                       int64_t N, int64_t K, void *out, sb_dtype out_dtype, hipStream_t stream) {
+    if (M == 0 || N == 0) return hipSuccess;
+    GemmI8Args args{aq, bq, state_row, state_tensor, nullptr, out, (int)M, (int)N, (int)K, 0, 0, 8, bias, gamma};
+    static std::atomic<bool> attr_set[6];  // zero-initialized
+    const bool bf = out_dtype == SB_BF16;
+    if (K % 128 != 0)
+        return bf ? launch<K64>(gemm_i8p_k64_bf16, &attr_set[0], args, stream)
+                  : launch<K64>(gemm_i8p_k64_f32, &attr_set[1], args, stream);
+    if (few_tiles(M, N))
+        return bf ? launch<K128S>(gemm_i8p_k128s_bf16, &attr_set[2], args, stream)
+                  : launch<K128S>(gemm_i8p_k128s_f32, &attr_set[3], args, stream);
+    return bf ? launch<K128Q>(gemm_i8p_k128_bf16, &attr_set[4], args, stream)
+              : launch<K128Q>(gemm_i8p_k128_f32, &attr_set[5], args, stream);
 }
 
 hipError_t launch_gemm_i8_dequant(const int8_t *aq, const float *state_row, const int8_t *bq,

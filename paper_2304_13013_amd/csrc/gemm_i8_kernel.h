@@ -104,6 +104,8 @@ struct GemmI8Args {
     int M, N, K;  // M*K and N*K must stay below 2^32 (32-bit buffer offsets)
     int tiles_m, tiles_n;
     int group_m;  // tile rows per group of the tile walk
+    const float *bias;   // [N] or nullptr; POST instances only: out = gamma[j] * (y + bias[j]), bias first
+    const float *gamma;  // [N] or nullptr
 };
 
 // Output tile visited by workgroup `wg` in its `round`-th iteration.  Tiles are numbered along groups of group_m
@@ -166,11 +168,14 @@ __device__ __forceinline__ void wait_stage(int later) {
 // What one wave does: an (MT*32) x 64 part of the workgroup's tile, rows from wm0.  Every role runs the same
 // sequence of barriers.
 // COLSCALE: out[i,j] = (float)acc * fl(state_row[i] * fl(state_col[j] / 127^2)) instead of the tensor-wise scale.
+// POST: the dequantized value y continues through the linear layer's bias and the block's layer-scale before it is
+// stored: fl(y + bias[j]) if p.bias is given, then fl(gamma[j] * that) if p.gamma is given.  The two vectors are
+// fetched at the start of the epilogue (64 more registers there, so these instances use the even wave split).
 //
 // The float8 product runs the same pipeline with one MFMA per 64 k-values: an operand fragment is then 32 bytes per
 // lane, fetched by the two 16-byte LDS reads that two consecutive int8 k-steps would issue.  Which 64 k-values a
 // lane's registers hold does not matter as long as both operands use the same assignment, which they do.
-template <class C, int OUT, int MT, bool COLSCALE, int MATH = MATH_I8>
+template <class C, int OUT, int MT, bool COLSCALE, int MATH = MATH_I8, bool POST = false>
 __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const int wave, const int wm0) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     typedef __attribute__((address_space(3))) void lds_void;
@@ -182,6 +187,7 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
     typedef typename std::conditional<F8, v16f, v16i>::type AccT;
     typedef typename std::conditional<F8, v8i, v4i>::type FragT;
     static_assert(!F8 || (OUT != OUT_I32 && !COLSCALE), "the float8 product has dequantized outputs and a tensor-wise weight state");
+    static_assert(!POST || (OUT != OUT_I32 && !COLSCALE && !F8), "bias / layer-scale follow the tensor-wise int8 dequantization");
     static_assert(KKG >= 2 && KKG % 2 == 0, "the register double-buffering alternates per k-step group within a stage");
     constexpr int NSCALE = OUT != OUT_I32 ? MT + (COLSCALE ? C::NT * 4 : 0) : 0;  // per-lane scale loads per tile
     constexpr int NFRAG = MT + C::NT;
@@ -482,6 +488,46 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
         const int m_base = tm * C::BM + wm0, n_base = tn * C::BN + wn0;
         const bool interior = (tm + 1) * C::BM <= p.M && (tn + 1) * C::BN <= p.N;
 
+        // Bias and layer-scale of this lane's accumulator quads (columns nt*32 + 8q + 4*(lane/32) .. +3).  Waiting for
+        // them drains the vector-memory queue, the next tile's first stages included; they have mostly landed by now.
+        v4f pbias[POST ? C::NT : 1][4], pgamma[POST ? C::NT : 1][4];
+        const bool has_bias = POST && p.bias != nullptr, has_gamma = POST && p.gamma != nullptr;
+        if (POST) {
+#pragma unroll
+            for (int nt = 0; nt < C::NT; ++nt)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int col = min(tn * C::BN + wn0 + nt * 32 + 8 * q + 4 * fhalf, p.N - 4);
+                    pbias[nt][q] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+                    pgamma[nt][q] = v4f{1.0f, 1.0f, 1.0f, 1.0f};
+                    if (has_bias) {
+                        const float *src = p.bias + col;
+                        asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(pbias[nt][q]) : "v"(src) : "memory");
+                    }
+                    if (has_gamma) {
+                        const float *src = p.gamma + col;
+                        asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(pgamma[nt][q]) : "v"(src) : "memory");
+                    }
+                }
+            note_vmem((has_bias ? C::NT * 4 : 0) + (has_gamma ? C::NT * 4 : 0));
+            wait_vmem_at_most(0);
+#pragma unroll
+            for (int nt = 0; nt < C::NT; ++nt)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    asm volatile("" : "+v"(pbias[nt][q]));
+                    asm volatile("" : "+v"(pgamma[nt][q]));
+                }
+        }
+        // The value stored for accumulator element e of quad (nt, q) in 32-row block mt.
+        auto finish = [&](float y, int nt, int q, int e) -> float {
+            if (POST) {
+                if (has_bias) y = y + pbias[nt][q][e];      // -0 + 0 would lose the sign: skipped, not added, when absent
+                if (has_gamma) y = pgamma[nt][q][e] * y;
+            }
+            return y;
+        };
+
         // Row scales r_i = state_row[i] * (state_tensor / 127^2), one per lane per 32-row block.
         float rscale[MT];
         if (OUT != OUT_I32) {
@@ -525,8 +571,9 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
                         v4f v;
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
-                            v[e] = (float)(acc[mt][nt][4 * q + e]) *
-                                   (COLSCALE ? rscale[mt] * scol[nt][q][e] : rscale[mt]);
+                            v[e] = finish((float)(acc[mt][nt][4 * q + e]) *
+                                              (COLSCALE ? rscale[mt] * scol[nt][q][e] : rscale[mt]),
+                                          nt, q, e);
                         packed[nt * 4 + q] = __builtin_convertvector(v, v4bf);
                     }
             };
@@ -590,8 +637,9 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
                                 v4f v;
 #pragma unroll
                                 for (int e = 0; e < 4; ++e)
-                                    v[e] = (float)(acc[mt][nt][4 * q + e]) *
-                                   (COLSCALE ? rscale[mt] * scol[nt][q][e] : rscale[mt]);
+                                    v[e] = finish((float)(acc[mt][nt][4 * q + e]) *
+                                                      (COLSCALE ? rscale[mt] * scol[nt][q][e] : rscale[mt]),
+                                                  nt, q, e);
                                 *reinterpret_cast<v4f *>(static_cast<float *>(p.out) + (int64_t)gr * p.N + gc) = v;
                             } else {
                                 v4i v;
@@ -613,15 +661,15 @@ __device__ __forceinline__ void gemm_i8_dequant_role(const GemmI8Args &p, const 
 
 // The kernel body.  It is a __device__ template called from non-template __global__ entry points: a __global__
 // template that uses device-only buffer builtins does not instantiate in the host pass.
-template <class C, int OUT, bool COLSCALE = false, int MATH = MATH_I8>
+template <class C, int OUT, bool COLSCALE = false, int MATH = MATH_I8, bool POST = false>
 __device__ __forceinline__ void gemm_i8_dequant_body(const GemmI8Args &p) {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform: what derives from it is scalar
     if (C::MT_LOADER == C::MT_EVEN)
-        gemm_i8_dequant_role<C, OUT, C::MT_EVEN, COLSCALE, MATH>(p, wave, (wave / C::WAVES_N) * C::WTM);
+        gemm_i8_dequant_role<C, OUT, C::MT_EVEN, COLSCALE, MATH, POST>(p, wave, (wave / C::WAVES_N) * C::WTM);
     else if (wave < C::LOADERS)
-        gemm_i8_dequant_role<C, OUT, C::MT_LOADER, COLSCALE, MATH>(p, wave, 0);
+        gemm_i8_dequant_role<C, OUT, C::MT_LOADER, COLSCALE, MATH, POST>(p, wave, 0);
     else
-        gemm_i8_dequant_role<C, OUT, 2 * C::MT_EVEN - C::MT_LOADER, COLSCALE, MATH>(p, wave, C::MT_LOADER * 32);
+        gemm_i8_dequant_role<C, OUT, 2 * C::MT_EVEN - C::MT_LOADER, COLSCALE, MATH, POST>(p, wave, C::MT_LOADER * 32);
 }
 
 // Launch geometry shared by the entry points: a persistent grid, a multiple of the XCD count, at most one workgroup

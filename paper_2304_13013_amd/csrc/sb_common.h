@@ -48,6 +48,11 @@ int num_compute_units();
 hipError_t launch_gemm_i8_dequant(const int8_t *aq, const float *state_row, const int8_t *bq,
                                   const float *state_tensor, const float *state_col, int64_t M, int64_t N,
                                   int64_t K, void *out, sb_dtype out_dtype, hipStream_t stream);
+// Tensor-wise int8 product whose dequantized value continues through y + bias[j] and gamma[j] * (.) (either vector may
+// be nullptr); out SB_BF16 or SB_F32.
+hipError_t launch_gemm_i8_dequant_post(const int8_t *aq, const float *state_row, const int8_t *bq,
+                                       const float *state_tensor, const float *bias, const float *gamma, int64_t M,
+                                       int64_t N, int64_t K, void *out, sb_dtype out_dtype, hipStream_t stream);
 // 8-bit float product (fmt 0: E4M3, 1: E5M2 per operand): out[i,j] = (state_row[i] * state_tensor[0]) * sum_k a b.
 // K % 128 == 0; out SB_BF16 or SB_F32.
 hipError_t launch_gemm_f8_dequant(const uint8_t *aq, int fmt_a, const float *state_row, const uint8_t *bq, int fmt_b,

@@ -106,6 +106,47 @@ int switchback_matmul_int8_dequant(const int8_t *aq, const float *state_row, con
                                                static_cast<hipStream_t>(stream)));
 }
 
+int switchback_matmul_int8_dequant_bias_layerscale(const int8_t *aq, const float *state_row, const int8_t *bq,
+                                                   const float *state_tensor, const float *bias, const float *gamma,
+                                                   int64_t M, int64_t N, int64_t K, void *out, sb_dtype out_dtype,
+                                                   void *stream) {
+    if (M < 0 || N <= 0 || K <= 0 || (out_dtype != SB_BF16 && out_dtype != SB_F32)) return SB_INVALID_ARG;
+    if (K % 64 || N % 64 || K > kMaxIntK || N > kMaxIntK || M > (int64_t)1 << 30) return SB_UNSUPPORTED_SHAPE;
+    if ((M + 256) * K >= (int64_t)1 << 32 || (N + 256) * K >= (int64_t)1 << 32) return SB_UNSUPPORTED_SHAPE;
+    if (M * N * 2 >= (int64_t)1 << 32) return SB_UNSUPPORTED_SHAPE;
+    if (M == 0) return SB_OK;
+    if (!ok_ptr(aq) || !ok_ptr(bq) || !ok_ptr(out) || state_row == nullptr || state_tensor == nullptr)
+        return SB_INVALID_ARG;
+    if ((bias != nullptr && !aligned16(bias)) || (gamma != nullptr && !aligned16(gamma))) return SB_INVALID_ARG;
+    return from_hip(sb::launch_gemm_i8_dequant_post(aq, state_row, bq, state_tensor, bias, gamma, M, N, K, out,
+                                                    out_dtype, static_cast<hipStream_t>(stream)));
+}
+
+int switchback_forward_bias_layerscale(const void *x_bf16, const void *w_bf16, const float *bias, const float *gamma,
+                                       int64_t b, int64_t n, int64_t m, void *y, sb_dtype y_dtype,
+                                       const sb_saved *saved, void *ws, size_t ws_bytes, void *stream) {
+    int st = layer_shape_status(b, n, m);
+    if (st != SB_OK) return st;
+    if ((y_dtype != SB_BF16 && y_dtype != SB_F32) || saved == nullptr) return SB_INVALID_ARG;
+    if (!ok_ptr(w_bf16) || !ok_ptr(saved->wq) || !ok_ptr(saved->wq_t) || saved->state_w == nullptr)
+        return SB_INVALID_ARG;
+    if (b > 0 && (!ok_ptr(x_bf16) || !ok_ptr(y) || !ok_ptr(saved->xq) || saved->state_x == nullptr))
+        return SB_INVALID_ARG;
+    if ((bias != nullptr && !aligned16(bias)) || (gamma != nullptr && !aligned16(gamma))) return SB_INVALID_ARG;
+    if (ws == nullptr || !aligned16(ws)) return SB_INVALID_ARG;
+    if (ws_bytes < switchback_workspace_bytes(SB_OP_FORWARD, b, n, m)) return SB_WORKSPACE_TOO_SMALL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // Algorithm 1's forward pass; the product's epilogue continues with the layer's bias and the block's layer-scale.
+    hipError_t e = sb::launch_quantize_tensorwise(w_bf16, m, n, saved->wq, saved->wq_t, saved->state_w,
+                                                  static_cast<unsigned int *>(ws), s);
+    if (e != hipSuccess) return SB_HIP_ERROR;
+    if (b == 0) return SB_OK;
+    e = sb::launch_quantize_rowwise(x_bf16, b, n, saved->xq, saved->state_x, s);
+    if (e != hipSuccess) return SB_HIP_ERROR;
+    return from_hip(sb::launch_gemm_i8_dequant_post(saved->xq, saved->state_x, saved->wq, saved->state_w, bias, gamma,
+                                                    b, m, n, y, y_dtype, s));
+}
+
 int switchback_forward(const void *x_bf16, const void *w_bf16, int64_t b, int64_t n, int64_t m, void *y,
                        sb_dtype y_dtype, const sb_saved *saved, void *ws, size_t ws_bytes, void *stream) {
     int st = layer_shape_status(b, n, m);

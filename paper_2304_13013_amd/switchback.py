@@ -54,6 +54,9 @@ def load_library():
     lib.switchback_quantize_tensorwise.argtypes = [vp, i64, i64, vp, vp, vp, vp, sz, vp]
     lib.switchback_matmul_int8_dequant.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, ci, vp]
     lib.switchback_forward.argtypes = [vp, vp, i64, i64, i64, vp, ci, ctypes.POINTER(SbSaved), vp, sz, vp]
+    lib.switchback_matmul_int8_dequant_bias_layerscale.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, vp, ci, vp]
+    lib.switchback_forward_bias_layerscale.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, ci, ctypes.POINTER(SbSaved),
+                                                       vp, sz, vp]
     lib.switchback_forward_static.argtypes = [vp, vp, i64, i64, i64, vp, ci, ctypes.POINTER(SbSaved), vp]
     lib.switchback_backward_input.argtypes = [vp, ctypes.POINTER(SbSaved), i64, i64, i64, vp, ci, vp, vp, vp]
     lib.switchback_backward_weight.argtypes = [vp, vp, i64, i64, i64, vp, ci, vp, sz, vp]
@@ -83,7 +86,8 @@ def load_library():
     lib.switchback_status_string.argtypes = [ci]
     lib.switchback_status_string.restype = ctypes.c_char_p
     for name in ("switchback_quantize_rowwise", "switchback_quantize_tensorwise", "switchback_matmul_int8_dequant",
-                 "switchback_forward", "switchback_forward_static", "switchback_backward_input", "switchback_backward_weight",
+                 "switchback_forward", "switchback_forward_static", "switchback_backward_input",
+                 "switchback_matmul_int8_dequant_bias_layerscale", "switchback_forward_bias_layerscale", "switchback_backward_weight",
                  "switchback_dequantize_rowwise", "switchback_backward_weight_m",
                  "switchback_quantize_colwise_transpose", "switchback_matmul_int8_dequant_rc",
                  "switchback_forward_q", "switchback_backward_input_q", "switchback_stable_adamw_step",
@@ -234,6 +238,49 @@ def forward(x, w, bufs=None, y=None, y_dtype=torch.bfloat16):
     _check(lib.switchback_forward(_dev(x, torch.bfloat16, 2), _dev(w, torch.bfloat16, 2), b, n, m,
                                   _dev(y, y_dtype, 2), _SB_DTYPE[y_dtype], ctypes.byref(bufs.saved),
                                   _ptr(bufs.ws_fwd), bufs.ws_fwd.numel(), _stream()))
+    return y, bufs
+
+
+def _vec(v, n, device, name):
+    """An optional f32 [n] device vector -> pointer (None -> NULL)."""
+    if v is None:
+        return None
+    _out(v, (n,), torch.float32, device, name)
+    return _dev(v, torch.float32, 1)
+
+
+def matmul_int8_dequant_bias_layerscale(aq, state_row, bq, state_tensor, bias=None, gamma=None,
+                                        out_dtype=torch.bfloat16, out=None):
+    """out[i,j] = gamma[j] * (state_tensor/127^2 * state_row[i] * sum_k aq[i,k] bq[j,k] + bias[j]); bias, gamma f32 [N]
+    or None."""
+    lib = load_library()
+    M, K = aq.shape
+    N = bq.shape[0]
+    if bq.shape[1] != K:
+        raise SwitchBackError("contraction lengths differ")
+    out = _out(out, (M, N), out_dtype, aq.device, "out")
+    _out(state_row, (M,), torch.float32, aq.device, "state_row")
+    _check(lib.switchback_matmul_int8_dequant_bias_layerscale(
+        _dev(aq, torch.int8, 2), _dev(state_row, torch.float32), _dev(bq, torch.int8, 2),
+        _dev(state_tensor, torch.float32), _vec(bias, N, aq.device, "bias"), _vec(gamma, N, aq.device, "gamma"),
+        M, N, K, _dev(out, out_dtype, 2), _SB_DTYPE[out_dtype], _stream()))
+    return out
+
+
+def forward_bias_layerscale(x, w, bias=None, gamma=None, bufs=None, y=None, y_dtype=torch.bfloat16):
+    """Algorithm 1 forward with the layer's bias and the block's layer-scale in the epilogue: gamma * (X W^T + bias)."""
+    lib = load_library()
+    b, n = x.shape
+    m = w.shape[0]
+    if w.shape[1] != n:
+        raise SwitchBackError("x [b,n] and w [m,n] disagree on n")
+    bufs = LayerBuffers(b, n, m, x.device) if bufs is None else bufs
+    _check_bufs(bufs, b, n, m)
+    y = _out(y, (b, m), y_dtype, x.device, "y")
+    _check(lib.switchback_forward_bias_layerscale(
+        _dev(x, torch.bfloat16, 2), _dev(w, torch.bfloat16, 2), _vec(bias, m, x.device, "bias"),
+        _vec(gamma, m, x.device, "gamma"), b, n, m, _dev(y, y_dtype, 2), _SB_DTYPE[y_dtype], ctypes.byref(bufs.saved),
+        _ptr(bufs.ws_fwd), bufs.ws_fwd.numel(), _stream()))
     return y, bufs
 
 

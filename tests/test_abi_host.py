@@ -148,6 +148,17 @@ def test_bad_arguments_are_rejected_before_launch(lib):
     assert lib.switchback_forward_static(fake, fake, 8, 100, 64, fake, 0, sp, null) == SHAPE
     assert lib.switchback_forward_static(null, fake, 8, 64, 64, fake, 0, sp, null) == INVALID
     assert lib.switchback_forward_static(fake, fake, 8, 64, 64, fake, 9, sp, null) == INVALID
+    bl = lib.switchback_matmul_int8_dequant_bias_layerscale
+    assert bl(fake, fake, fake, fake, fake, fake, 8, 64, 32, fake, 0, null) == SHAPE
+    assert bl(fake, fake, fake, fake, odd, fake, 8, 64, 64, fake, 0, null) == INVALID               # misaligned bias
+    assert bl(fake, fake, fake, fake, null, null, 8, 64, 64, fake, 2, null) == INVALID              # no raw mode
+    assert bl(fake, null, fake, fake, null, null, 8, 64, 64, fake, 0, null) == INVALID
+    assert bl(null, null, null, null, null, null, 0, 64, 64, null, 0, null) == 0
+    fbl = lib.switchback_forward_bias_layerscale
+    assert fbl(fake, fake, fake, fake, 8, 100, 64, fake, 0, sp, fake, 1 << 20, null) == SHAPE
+    assert fbl(fake, fake, fake, odd, 8, 64, 64, fake, 0, sp, fake, 1 << 20, null) == INVALID
+    assert fbl(fake, fake, null, null, 8, 64, 64, fake, 0, sp, fake, 8, null) == WS
+    assert fbl(fake, fake, null, null, 8, 64, 64, fake, 2, sp, fake, 1 << 20, null) == INVALID
     # the measurement aids validate their arguments too
     ceil = lib.switchback_ceiling_mfma
     assert ceil(0, fake, 1024, fake, 1024, 0, 8, 10, fake, None, null) == INVALID                   # no workgroups

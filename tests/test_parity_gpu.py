@@ -140,6 +140,81 @@ def test_dequantized_product(oracle, M, N, K):
 
 
 # ---------------------------------------------------------------------------------------------------------------
+# bias and layer-scale in the epilogue of the int8 product: gamma * (y + bias), bias first, one rounding each.  The
+# kernel evaluates the oracle's operation sequence, so binary32 results are compared within one ulp of the dequantized
+# value carried through the two operations, and must be bit-identical wherever the dequantized value is.
+# ---------------------------------------------------------------------------------------------------------------
+
+def assert_bias_layerscale(got32, got_bf16_bits, acc, srow, sw, bias, gamma, oracle):
+    y = oracle.dequantize(acc, srow, np.float32(sw))
+    ref = oracle.bias_layerscale(y, bias, gamma)
+    g = np.ones(acc.shape[1], np.float32) if gamma is None else np.abs(gamma)
+    tol = g[None, :].astype(np.float64) * ulp(y) + ulp(ref)         # 1 ulp of y through the multiply, then one rounding
+    assert np.all(np.abs(got32.astype(np.float64) - ref) <= tol)
+    assert np.array_equal(got32.view(np.uint32), ref.view(np.uint32))  # same operation order: the bits match
+    np.testing.assert_array_equal(got_bf16_bits, oracle.round_to_bf16(ref))
+
+
+@pytest.mark.parametrize("which", ["both", "bias", "gamma", "neither"])
+@pytest.mark.parametrize("M,N,K", [(300, 320, 192), (512, 1024, 256), (4096, 2304, 256), (1000, 4160, 320)])
+def test_bias_layerscale_product(oracle, M, N, K, which):
+    """All three kernel instances: 64-byte k-steps (K = 192, 320), the 128x128 tile (8 large tiles), the 256x256 tile
+    over more than one round of a 256-workgroup grid would need > 256 tiles; 144 tiles run one round."""
+    rng = np.random.default_rng(M + N + K)
+    a = rng.integers(-127, 128, size=(M, K)).astype(np.int8)
+    b = rng.integers(-127, 128, size=(N, K)).astype(np.int8)
+    srow = (rng.random(M) * 4 + 1e-3).astype(np.float32)
+    srow[M // 3] = 0.0                                              # zero product row: output gamma * bias
+    bias = (rng.standard_normal(N) * 3).astype(np.float32) if which in ("both", "bias") else None
+    gamma = rng.standard_normal(N).astype(np.float32) if which in ("both", "gamma") else None
+    if gamma is not None:
+        gamma[5] = 0.0                                              # a zero-initialised layer-scale entry
+    dev = lambda v: None if v is None else torch.from_numpy(v).to(DEV)
+    args = (torch.from_numpy(a).to(DEV), dev(srow), torch.from_numpy(b).to(DEV), torch.tensor([0.21875], device=DEV),
+            dev(bias), dev(gamma))
+    o32 = host(sb.matmul_int8_dequant_bias_layerscale(*args, out_dtype=torch.float32))
+    obf = bits_of(sb.matmul_int8_dequant_bias_layerscale(*args, out_dtype=torch.bfloat16))
+    assert_bias_layerscale(o32, obf, oracle.matmul_int8(a, b), srow, 0.21875, bias, gamma, oracle)
+    if gamma is not None:
+        assert not o32[:, 5].any()
+    if which == "neither":                                          # then it is the plain product, bit for bit
+        np.testing.assert_array_equal(obf, bits_of(sb.matmul_int8_dequant(*args[:4])))
+
+
+def test_bias_layerscale_layer(oracle):
+    """The layer call on the tiny workload with edge rows, and on the ViT-H/14 output projection at full size (645
+    tiles, three per workgroup) on one token row per 32-row block; a zero-initialised gamma gives an all-zero output."""
+    d = I.make_layer_inputs("tiny")
+    I.plant_edge_rows(d["x"])
+    rng = np.random.default_rng(3)
+    m = d["w"].shape[0]
+    bias, gamma = rng.standard_normal(m).astype(np.float32), (rng.standard_normal(m) * 0.1).astype(np.float32)
+    x, w = to_dev(d["x"]), to_dev(d["w"])
+    bd, gd = torch.from_numpy(bias).to(DEV), torch.from_numpy(gamma).to(DEV)
+    y32, bufs = sb.forward_bias_layerscale(x, w, bd, gd, y_dtype=torch.float32)
+    ybf, _ = sb.forward_bias_layerscale(x, w, bd, gd, bufs=bufs)
+    y0, _ = sb.forward_bias_layerscale(x, w, bd, torch.zeros_like(gd), bufs=bufs)
+    f = oracle.forward(d["x"], d["w"])
+    np.testing.assert_array_equal(host(bufs.xq), f["xq"])
+    np.testing.assert_array_equal(host(bufs.wq_t), f["wq_t"])
+    assert_bias_layerscale(host(y32), bits_of(ybf), f["acc"], f["state_x"], f["state_w"], bias, gamma, oracle)
+    assert not (bits_of(y0) & 0x7fff).any()
+
+    L = I.CONFIGS["vit_h14"].layers[1]
+    d = I.make_layer_inputs("vit_h14", 1, which=("x", "w"))
+    bias, gamma = rng.standard_normal(L.m).astype(np.float32), (rng.standard_normal(L.m) * 0.1).astype(np.float32)
+    rows = one_row_per_block(L.b, 32, rng)
+    idx = torch.from_numpy(rows).to(DEV)
+    bd, gd = torch.from_numpy(bias).to(DEV), torch.from_numpy(gamma).to(DEV)
+    x, w = to_dev(d["x"]), to_dev(d["w"])
+    y32, bufs = sb.forward_bias_layerscale(x, w, bd, gd, y_dtype=torch.float32)
+    ybf, _ = sb.forward_bias_layerscale(x, w, bd, gd, bufs=bufs)
+    xq, sx = oracle.quantize_rowwise(d["x"][rows])
+    wq, _, sw = oracle.quantize_tensorwise(d["w"])
+    assert_bias_layerscale(host(y32[idx]), bits_of(ybf[idx]), oracle.matmul_int8(xq, wq), sx, sw, bias, gamma, oracle)
+
+
+# ---------------------------------------------------------------------------------------------------------------
 # SwitchBackM: row-wise dequantization (bit-exact) and the weight gradient built on it
 # ---------------------------------------------------------------------------------------------------------------
 
