@@ -292,6 +292,32 @@ def main():
         ceilings["mfma_float8_workload_codes"] = round(
             ceiling(sb.SB_CEILING_F8, big["bufs"].xq.view(torch.uint8), big["bufs"].wq.view(torch.uint8)), 1)
         ceilings["mfma_float8_zero_operands"] = round(ceiling(sb.SB_CEILING_F8, zeros, zeros), 1)
+    # The product kernel's own main loop on the workload's codes, with the tile boundary amortized away: one 256x256 tile
+    # per workgroup (4096 x 4096 outputs) and a contraction of 32768, i.e. 256 k-tiles per epilogue instead of 10.
+    # What separates this figure from the matrix-instruction loop above is the operand traffic (L2 -> LDS -> registers);
+    # what separates the workload's products from this figure is the tile boundary (epilogue, output stores) and
+    # the rounds that do not fill the GPU.
+    sb.forward(big["x"], big["w"], bufs=big["bufs"], y=big["y"])
+    sb.backward_input(big["dy"], big["bufs"], dx=big["dx"])
+    need = 4096 * 32768
+    if big["bufs"].gq.numel() >= need and big["bufs"].wq.numel() + big["bufs"].xq.numel() >= 0:
+        a_long = big["bufs"].gq.view(-1)[:need].view(4096, 32768)
+        b_src = torch.cat([big["bufs"].wq.view(-1), big["bufs"].wq_t.view(-1)])
+        b_long = b_src.repeat(-(-need // b_src.numel()))[:need].view(4096, 32768).contiguous()
+        out_long = torch.empty((4096, 4096), dtype=torch.bfloat16, device=dev)
+        run = lambda: sb.matmul_int8_dequant(a_long, big["bufs"].state_g[:4096].contiguous(), b_long,
+                                             big["bufs"].state_w, out=out_long)
+        run()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            run()
+        e1.record()
+        torch.cuda.synchronize()
+        ceilings["gemm_int8_main_loop_only_workload_codes"] = round(
+            5 * 2.0 * 4096 * 4096 * 32768 / e0.elapsed_time(e1) / 1e9, 1)
+        del a_long, b_long, b_src, out_long
     src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(3)
     dst = torch.empty_like(src)
     sb.ceiling_copy(src, dst)

@@ -1,6 +1,8 @@
 // Host-side dispatch of the bf16 weight-gradient GEMM (kernel: gemm_bf16_tn_kernel.h) and its split-K reduction.
 #include "gemm_bf16_tn_kernel.h"
 
+#include <atomic>
+
 namespace sb {
 namespace {
 
@@ -24,7 +26,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const v4f *__restric
 
 // Splits: fill the compute units in whole rounds with as few splits as that takes.
 int choose_splits(int64_t b, int tiles) {
-    const int ncu = 256;
+    const int ncu = num_compute_units();
     int best = 1;
     double best_score = -1.0;
     for (int s = 1; s <= MAX_SPLITS; ++s) {
@@ -53,13 +55,13 @@ size_t gemm_bf16_tn_workspace_bytes(int64_t b, int64_t n, int64_t m) {
 
 hipError_t launch_gemm_bf16_tn(const void *dy, const void *x, int64_t b, int64_t n, int64_t m, void *dw,
                                sb_dtype dw_dtype, void *ws, hipStream_t stream) {
-    static bool attr_set = false;
+    static std::atomic<bool> attr_set{false};  // a second set by a racing host thread is harmless
     void (*kernel)(GemmBf16Args) = gemm_bf16_tn_kernel;
-    if (!attr_set) {
+    if (!attr_set.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     GemmBf16Args a;
     a.dy = static_cast<const unsigned short *>(dy);
@@ -76,8 +78,8 @@ hipError_t launch_gemm_bf16_tn(const void *dy, const void *x, int64_t b, int64_t
     a.out = dw;
     a.out_bf16 = dw_dtype == SB_BF16;
     const int total = a.tiles_m * a.tiles_n * a.splits;
-    const int per_xcd = (total + 7) / 8;
-    const int grid = 8 * (per_xcd < 32 ? per_xcd : 32);  // persistent: at most one workgroup per compute unit
+    const int per_xcd = (total + 7) / 8, cus_per_xcd = num_compute_units() / 8 > 0 ? num_compute_units() / 8 : 1;
+    const int grid = 8 * (per_xcd < cus_per_xcd ? per_xcd : cus_per_xcd);  // persistent: at most one workgroup per compute unit
     gemm_bf16_tn_kernel<<<grid, Cfg::THREADS, Cfg::LDS_BYTES, stream>>>(a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || a.splits == 1) return e;
