@@ -15,7 +15,8 @@
 // The X-side tile is the MFMA's first operand and the dY-side tile its second, so a lane owns one dW row.
 //
 // The contraction is long (b ~ 32k) and the output small, so work items are (split, tile) pairs (split-K); they are
-// dealt to the XCDs in split-major runs so that the workgroups sharing an L2 read the same token range.  With more
+// dealt to the XCDs in split-major runs of neighbouring tiles so that the workgroups sharing an L2 read the same token
+// range and few distinct operand panels.  With more
 // than one split the partial sums go to a binary32 workspace [split][m][n] and a second kernel adds them in split
 // order (deterministic) and converts to the output type.
 #pragma once
@@ -169,17 +170,26 @@ __device__ __forceinline__ void gemm_bf16_tn_role(const GemmBf16Args &p, const i
         }
     };
 
-    // Work items: XCD x (workgroup id % 8) owns the contiguous run [x*per_xcd, (x+1)*per_xcd) of split-major items.
+    // Work items are (split, tile) pairs numbered split-major, the tiles of a split walked along the SHORTER side of
+    // the tile grid first, so that 32 consecutive items form a compact patch (about 6 x 5 tiles: 12 operand panels for
+    // 32 tiles; walking a 5 x 20 grid along its long side touches 22).  Round r of the persistent grid takes items
+    // [r * grid, (r + 1) * grid), and XCD x (workgroup id % 8) the x-th run of grid / 8 consecutive items of it: the
+    // workgroups sharing an L2 read one token range and neighbouring tiles, and all XCDs stream the same few token
+    // ranges at the same time, so what one fetched from HBM the others find in the last-level cache.
     const int tiles = p.tiles_m * p.tiles_n, total = tiles * p.splits;
-    const int per_xcd = (total + 7) / 8, xcd = blockIdx.x & 7, slots = gridDim.x >> 3;
-    const int run_end = min(total, (xcd + 1) * per_xcd);
+    const int xcd = blockIdx.x & 7, slots = gridDim.x >> 3;
     auto item_of = [&](int round, int *tm, int *tn, int *split) -> bool {
-        const int item = xcd * per_xcd + (blockIdx.x >> 3) + round * slots;
-        if (item >= run_end) return false;
+        const int item = round * (int)gridDim.x + xcd * slots + (blockIdx.x >> 3);
+        if (item >= total) return false;
         *split = item / tiles;
         const int tile = item % tiles;
-        *tm = tile / p.tiles_n;
-        *tn = tile % p.tiles_n;
+        if (p.tiles_m < p.tiles_n) {
+            *tm = tile % p.tiles_m;
+            *tn = tile / p.tiles_m;
+        } else {
+            *tm = tile / p.tiles_n;
+            *tn = tile % p.tiles_n;
+        }
         return true;
     };
     auto stages_of = [&](int split) -> int {
