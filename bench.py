@@ -24,11 +24,13 @@ PEAK = {"hbm_GBps": 8000.0, "int8_TOPs": 5000.0, "bf16_TFLOPs": 2500.0}
 # HBM-side bytes per launch (mean over the launches of one step) of each kernel group on the vit_h14 workload, from
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script (FETCH_SIZE x2, WRITE_SIZE x1 after calibration against
 # copy kernels of known size; summary and commands in profiles/bench_vit_h14_hbm_traffic.md).  Not re-measured at run
-# time; null for other workloads.
+# time: the table belongs to the kernels as they were when that profile was taken (tile walk, grid and split choices
+# decide the figures), and is null for other workloads.
 TRAFFIC_BYTES_PER_LAUNCH_VIT_H14 = {
-    "gemm_int8_dequant": 324.3e6 + 169.1e6,        # 8 launches per step; algorithmic mean 257.6e6
-    "gemm_bf16_weight_grad": 743.6e6 + 97.9e6,     # 4 launches per step, fp32 split-K partials included
-    "quantize_rowwise": 253.2e6,                   # 8 launches per step
+    "gemm_int8_dequant": 328.2e6 + 169.0e6,        # 8 launches per step; algorithmic mean 257.6e6
+    "gemm_bf16_weight_grad": 581.6e6 + 97.9e6,     # 4 launches per step, fp32 split-K partials included; the reduction
+                                                   # kernel of the same step adds 96.7e6 + 9.8e6; algorithmic 346.7e6
+    "quantize_rowwise": 253.3e6,                   # 8 launches per step
 }
 
 
@@ -44,6 +46,9 @@ def parse():
                          "rocprofv3 --pmc run of this command can scale FETCH_SIZE / WRITE_SIZE")
     ap.add_argument("--no-clocks", action="store_true",
                     help="skip the rocm-smi clock reading (it queues about a second of extra steps)")
+    ap.add_argument("--no-ceilings", action="store_true",
+                    help="skip the measured-ceilings leg (matrix-instruction loops, main-loop-only product, copy); "
+                         "measured_peak / frac_of_measured are then null")
     ap.add_argument("--cpu-sample-rows", type=int, default=0, help="token rows of the oracle sample (0 = auto)")
     return ap.parse_args()
 
@@ -277,62 +282,64 @@ def main():
         torch.cuda.synchronize()
         return work * reps / e0.elapsed_time(e1) / 1e9
 
-    big = max(layers, key=lambda t: t["L"].n * t["L"].m)
-    sb.forward(big["x"], big["w"], bufs=big["bufs"], y=big["y"])           # int8 codes back into the buffers
-    sb.backward_input(big["dy"], big["bufs"], dx=big["dx"])
-    zeros = torch.zeros(1 << 20, dtype=torch.uint8, device=dev)
-    ceilings = {
-        "mfma_int8_workload_codes": round(ceiling(sb.SB_CEILING_I8, big["bufs"].gq, big["bufs"].wq), 1),
-        "mfma_int8_zero_operands": round(ceiling(sb.SB_CEILING_I8, zeros, zeros), 1),
-        "mfma_bf16_workload_values": round(ceiling(sb.SB_CEILING_BF16, big["dy"], big["x"]), 1),
-        "mfma_bf16_zero_operands": round(ceiling(sb.SB_CEILING_BF16, zeros, zeros), 1),
-    }
-    if big["L"].n % 128 == 0 and big["L"].m % 128 == 0:
-        sb.forward_f8(big["x"], big["w"], bufs=big["bufs"], y=big["y"])
-        ceilings["mfma_float8_workload_codes"] = round(
-            ceiling(sb.SB_CEILING_F8, big["bufs"].xq.view(torch.uint8), big["bufs"].wq.view(torch.uint8)), 1)
-        ceilings["mfma_float8_zero_operands"] = round(ceiling(sb.SB_CEILING_F8, zeros, zeros), 1)
-    # The product kernel's own main loop on the workload's codes, with the tile boundary amortized away: one 256x256 tile
-    # per workgroup (4096 x 4096 outputs) and a contraction of 32768, i.e. 256 k-tiles per epilogue instead of 10.
-    # What separates this figure from the matrix-instruction loop above is the operand traffic (L2 -> LDS -> registers);
-    # what separates the workload's products from this figure is the tile boundary (epilogue, output stores) and
-    # the rounds that do not fill the GPU.
-    sb.forward(big["x"], big["w"], bufs=big["bufs"], y=big["y"])
-    sb.backward_input(big["dy"], big["bufs"], dx=big["dx"])
-    need = 4096 * 32768
-    if big["bufs"].gq.numel() >= need and big["bufs"].wq.numel() + big["bufs"].xq.numel() >= 0:
-        a_long = big["bufs"].gq.view(-1)[:need].view(4096, 32768)
-        b_src = torch.cat([big["bufs"].wq.view(-1), big["bufs"].wq_t.view(-1)])
-        b_long = b_src.repeat(-(-need // b_src.numel()))[:need].view(4096, 32768).contiguous()
-        out_long = torch.empty((4096, 4096), dtype=torch.bfloat16, device=dev)
-        run = lambda: sb.matmul_int8_dequant(a_long, big["bufs"].state_g[:4096].contiguous(), b_long,
-                                             big["bufs"].state_w, out=out_long)
-        run()
+    ceilings, measured = None, {"int8": None, "bf16": None, "f8": None, "bytes": None}
+    if not args.no_ceilings:
+        big = max(layers, key=lambda t: t["L"].n * t["L"].m)
+        sb.forward(big["x"], big["w"], bufs=big["bufs"], y=big["y"])           # int8 codes back into the buffers
+        sb.backward_input(big["dy"], big["bufs"], dx=big["dx"])
+        zeros = torch.zeros(1 << 20, dtype=torch.uint8, device=dev)
+        ceilings = {
+            "mfma_int8_workload_codes": round(ceiling(sb.SB_CEILING_I8, big["bufs"].gq, big["bufs"].wq), 1),
+            "mfma_int8_zero_operands": round(ceiling(sb.SB_CEILING_I8, zeros, zeros), 1),
+            "mfma_bf16_workload_values": round(ceiling(sb.SB_CEILING_BF16, big["dy"], big["x"]), 1),
+            "mfma_bf16_zero_operands": round(ceiling(sb.SB_CEILING_BF16, zeros, zeros), 1),
+        }
+        if big["L"].n % 128 == 0 and big["L"].m % 128 == 0:
+            sb.forward_f8(big["x"], big["w"], bufs=big["bufs"], y=big["y"])
+            ceilings["mfma_float8_workload_codes"] = round(
+                ceiling(sb.SB_CEILING_F8, big["bufs"].xq.view(torch.uint8), big["bufs"].wq.view(torch.uint8)), 1)
+            ceilings["mfma_float8_zero_operands"] = round(ceiling(sb.SB_CEILING_F8, zeros, zeros), 1)
+        # The product kernel's own main loop on the workload's codes, with the tile boundary amortized away: one 256x256 tile
+        # per workgroup (4096 x 4096 outputs) and a contraction of 32768, i.e. 256 k-tiles per epilogue instead of 10.
+        # What separates this figure from the matrix-instruction loop above is the operand traffic (L2 -> LDS -> registers);
+        # what separates the workload's products from this figure is the tile boundary (epilogue, output stores) and
+        # the rounds that do not fill the GPU.
+        sb.forward(big["x"], big["w"], bufs=big["bufs"], y=big["y"])
+        sb.backward_input(big["dy"], big["bufs"], dx=big["dx"])
+        need = 4096 * 32768
+        if big["bufs"].gq.numel() >= need:
+            a_long = big["bufs"].gq.view(-1)[:need].view(4096, 32768)
+            b_src = torch.cat([big["bufs"].wq.view(-1), big["bufs"].wq_t.view(-1)])
+            b_long = b_src.repeat(-(-need // b_src.numel()))[:need].view(4096, 32768).contiguous()
+            out_long = torch.empty((4096, 4096), dtype=torch.bfloat16, device=dev)
+            run = lambda: sb.matmul_int8_dequant(a_long, big["bufs"].state_g[:4096].contiguous(), b_long,
+                                                 big["bufs"].state_w, out=out_long)
+            run()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(5):
+                run()
+            e1.record()
+            torch.cuda.synchronize()
+            ceilings["gemm_int8_main_loop_only_workload_codes"] = round(
+                5 * 2.0 * 4096 * 4096 * 32768 / e0.elapsed_time(e1) / 1e9, 1)
+            del a_long, b_long, b_src, out_long
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(3)
+        dst = torch.empty_like(src)
+        sb.ceiling_copy(src, dst)
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         for _ in range(5):
-            run()
+            sb.ceiling_copy(src, dst)
         e1.record()
         torch.cuda.synchronize()
-        ceilings["gemm_int8_main_loop_only_workload_codes"] = round(
-            5 * 2.0 * 4096 * 4096 * 32768 / e0.elapsed_time(e1) / 1e9, 1)
-        del a_long, b_long, b_src, out_long
-    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(3)
-    dst = torch.empty_like(src)
-    sb.ceiling_copy(src, dst)
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(5):
-        sb.ceiling_copy(src, dst)
-    e1.record()
-    torch.cuda.synchronize()
-    ceilings["copy_read_plus_write_GBps"] = round(5 * 2.0 * src.numel() / e0.elapsed_time(e1) / 1e6, 1)
-    ceilings["unit"] = "T(FL)OP/s for the matrix-instruction loops (register-resident, no LDS or memory traffic), GB/s for the copy"
-    del src, dst
-    measured = {"int8": ceilings["mfma_int8_workload_codes"], "bf16": ceilings["mfma_bf16_workload_values"],
-                "f8": ceilings.get("mfma_float8_workload_codes"), "bytes": ceilings["copy_read_plus_write_GBps"]}
+        ceilings["copy_read_plus_write_GBps"] = round(5 * 2.0 * src.numel() / e0.elapsed_time(e1) / 1e6, 1)
+        ceilings["unit"] = "T(FL)OP/s for the matrix-instruction loops (register-resident, no LDS or memory traffic), GB/s for the copy"
+        del src, dst
+        measured = {"int8": ceilings["mfma_int8_workload_codes"], "bf16": ceilings["mfma_bf16_workload_values"],
+                    "f8": ceilings.get("mfma_float8_workload_codes"), "bytes": ceilings["copy_read_plus_write_GBps"]}
 
     kernels = {}
     for name, (ms, work, kind) in ops.items():
