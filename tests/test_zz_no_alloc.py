@@ -61,3 +61,39 @@ def test_forward_static_empty_batch_and_limits():
     assert lib.switchback_forward_static(fake, fake, 8, 16384, 16448, fake, 0, ctypes.byref(saved), None) == 2
     assert lib.switchback_forward_static(fake, fake, 8, 100, 64, fake, 0, ctypes.byref(saved), None) == 2
     assert lib.switchback_forward_static(None, fake, 8, 64, 64, fake, 0, ctypes.byref(saved), None) == 1
+
+
+def test_a_whole_step_replays_from_a_hip_graph():
+    """What the allocation-free forward is for: forward, input gradient and weight gradient of a layer captured into one
+    HIP graph (the library only enqueues kernels; it neither allocates, synchronizes nor records memset nodes).  Every
+    replay, with eager work and synchronizations in between, must reproduce the eager results bit for bit."""
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(73)
+    b, n, m = 1500, 1280, 2304
+    x, w, dy = draw(gen, (b, n), 1.0), draw(gen, (m, n), 0.03), draw(gen, (b, m), 0.1)
+    bufs = sb.LayerBuffers(b, n, m, DEV)
+    y, dx, dw = (torch.empty(s, dtype=torch.bfloat16, device=DEV) for s in ((b, m), (b, n), (m, n)))
+
+    def step():
+        sb.forward_static(x, w, bufs, y=y)
+        sb.backward_input(dy, bufs, dx=dx)
+        sb.backward_weight(dy, x, bufs, dw=dw)
+
+    step()                                                        # warm-up: one-time kernel attributes are set here
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in (y, dx, dw, bufs.xq, bufs.gq, bufs.wq_t, bufs.state_w)]
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for t in (y, dx, dw, bufs.xq, bufs.gq, bufs.wq_t):
+            t.fill_(1)                                            # eager work between the replays
+        bufs.state_w.fill_(-1.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for want, got in zip(ref, (y, dx, dw, bufs.xq, bufs.gq, bufs.wq_t, bufs.state_w)):
+            assert same_bits(want, got), "replay %d differs from the eager step" % rep
