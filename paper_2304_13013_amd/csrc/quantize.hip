@@ -111,11 +111,39 @@ __device__ __forceinline__ v2u quantize_chunk(v4u c, float t) {
     return out;
 }
 
+// The first pass of the tensor-wise quantizer (per-workgroup partial absmax of W) as a rider on a row-wise launch:
+// workgroups [first_block, first_block + nblocks) of the grid do it instead of a row.  The forward pass quantizes X
+// row-wise and W tensor-wise; the two are independent, and W's first pass is a few microseconds of work that is
+// mostly launch overhead when it runs alone.  nblocks == 0: no rider.
+struct TensorAbsmaxJob {
+    const v4u *w;
+    int64_t nchunks;
+    unsigned int *partials;
+    int nblocks, first_block;
+};
+
+__device__ __forceinline__ void absmax_partial_body(const v4u *__restrict__ w, int64_t nchunks,
+                                                    unsigned int *__restrict__ partials, int block, int nblocks,
+                                                    unsigned int *wave_max /* shared, 4 entries */) {
+    unsigned int m = 0;
+    const int64_t stride = (int64_t)nblocks * 256;
+    for (int64_t c = (int64_t)block * 256 + threadIdx.x; c < nchunks; c += stride) m = absmax_of_chunk(m, w[c]);
+    m = wave_max_u32(max(m & 0xffffu, m >> 16));
+    if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) partials[block] = max(max(wave_max[0], wave_max[1]), max(wave_max[2], wave_max[3]));
+}
+
 // ---- row-wise: one wavefront per row (cols <= 64*8*NCH) ---------------------------------------------------
 template <int NCH, int CODE>
 __global__ __launch_bounds__(256) void quantize_rowwise_wave_kernel(const v4u *__restrict__ x, int64_t rows,
                                                                     int chunks, v2u *__restrict__ q,
-                                                                    float *__restrict__ state) {
+                                                                    float *__restrict__ state, TensorAbsmaxJob job) {
+    __shared__ unsigned int rider_max[4];
+    if (job.nblocks > 0 && (int)blockIdx.x >= job.first_block) {  // uniform per workgroup
+        absmax_partial_body(job.w, job.nchunks, job.partials, (int)blockIdx.x - job.first_block, job.nblocks, rider_max);
+        return;
+    }
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= rows) return;  // whole wavefront leaves; the kernel has no block-level barrier
@@ -145,8 +173,12 @@ __global__ __launch_bounds__(256) void quantize_rowwise_wave_kernel(const v4u *_
 template <int NCH, int CODE>
 __global__ __launch_bounds__(256) void quantize_rowwise_block_kernel(const v4u *__restrict__ x, int chunks,
                                                                      v2u *__restrict__ q,
-                                                                     float *__restrict__ state) {
+                                                                     float *__restrict__ state, TensorAbsmaxJob job) {
     __shared__ unsigned int wave_max[4];
+    if (job.nblocks > 0 && (int)blockIdx.x >= job.first_block) {  // uniform per workgroup
+        absmax_partial_body(job.w, job.nchunks, job.partials, (int)blockIdx.x - job.first_block, job.nblocks, wave_max);
+        return;
+    }
     const int64_t row = blockIdx.x;
     const v4u *xr = x + row * chunks;
     v4u v[NCH];
@@ -177,8 +209,12 @@ __global__ __launch_bounds__(256) void quantize_rowwise_block_kernel(const v4u *
 template <int CODE>
 __global__ __launch_bounds__(256) void quantize_rowwise_wide_kernel(const v4u *__restrict__ x, int chunks,
                                                                     v2u *__restrict__ q,
-                                                                    float *__restrict__ state) {
+                                                                    float *__restrict__ state, TensorAbsmaxJob job) {
     __shared__ unsigned int wave_max[4];
+    if (job.nblocks > 0 && (int)blockIdx.x >= job.first_block) {  // uniform per workgroup
+        absmax_partial_body(job.w, job.nchunks, job.partials, (int)blockIdx.x - job.first_block, job.nblocks, wave_max);
+        return;
+    }
     const int64_t row = blockIdx.x;
     const v4u *xr = x + row * chunks;
     unsigned int m = 0;
@@ -198,15 +234,7 @@ __global__ __launch_bounds__(256) void quantize_rowwise_wide_kernel(const v4u *_
 __global__ __launch_bounds__(256) void absmax_partial_kernel(const v4u *__restrict__ w, int64_t nchunks,
                                                              unsigned int *__restrict__ partials) {
     __shared__ unsigned int wave_max[4];
-    unsigned int m = 0;
-    const int64_t stride = (int64_t)gridDim.x * 256;
-    for (int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x; c < nchunks; c += stride)
-        m = absmax_of_chunk(m, w[c]);
-    m = wave_max_u32(max(m & 0xffffu, m >> 16));
-    if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = m;
-    __syncthreads();
-    if (threadIdx.x == 0)
-        partials[blockIdx.x] = max(max(wave_max[0], wave_max[1]), max(wave_max[2], wave_max[3]));
+    absmax_partial_body(w, nchunks, partials, (int)blockIdx.x, (int)gridDim.x, wave_max);
 }
 
 // ---- tensor-wise pass 2: finish the absmax, quantize a 128x128 tile, emit it row-major and transposed ------
@@ -412,16 +440,27 @@ hipError_t launch_quantize_colwise_transpose(const void *w, int64_t rows, int64_
     return hipGetLastError();
 }
 
+// Workgroups of the tensor-wise quantizer's first pass for a matrix of this many 8-element chunks.
+int tensorwise_partial_blocks(int64_t nchunks) {
+    int nblocks = (int)((nchunks + 256 * 4 - 1) / (256 * 4));
+    if (nblocks > kTensorwisePartials) nblocks = kTensorwisePartials;
+    return nblocks < 1 ? 1 : nblocks;
+}
+
 template <int CODE>
 hipError_t launch_quantize_rowwise_t(const void *x, int64_t rows, int64_t cols, void *q, float *state,
-                                     hipStream_t stream) {
+                                     hipStream_t stream, TensorAbsmaxJob job = TensorAbsmaxJob{nullptr, 0, nullptr, 0, 0}) {
     const int chunks = (int)(cols / 8);
     const v4u *xp = static_cast<const v4u *>(x);
     v2u *qp = static_cast<v2u *>(q);
-    const unsigned int wave_grid = (unsigned int)((rows + 3) / 4), block_grid = (unsigned int)rows;
+    unsigned int wave_grid = (unsigned int)((rows + 3) / 4), block_grid = (unsigned int)rows;
+    // The rider's workgroups follow the rows' in the grid.
+    job.first_block = (int)(chunks <= 256 ? wave_grid : block_grid);
+    wave_grid += (unsigned int)job.nblocks;
+    block_grid += (unsigned int)job.nblocks;
 #define SB_WAVE(N)                                                                                          \
-    quantize_rowwise_wave_kernel<N, CODE><<<wave_grid, 256, 0, stream>>>(xp, rows, chunks, qp, state)
-#define SB_BLOCK(N) quantize_rowwise_block_kernel<N, CODE><<<block_grid, 256, 0, stream>>>(xp, chunks, qp, state)
+    quantize_rowwise_wave_kernel<N, CODE><<<wave_grid, 256, 0, stream>>>(xp, rows, chunks, qp, state, job)
+#define SB_BLOCK(N) quantize_rowwise_block_kernel<N, CODE><<<block_grid, 256, 0, stream>>>(xp, chunks, qp, state, job)
     if (chunks <= 64) SB_WAVE(1);
     else if (chunks <= 128) SB_WAVE(2);
     else if (chunks <= 192) SB_WAVE(3);
@@ -431,7 +470,7 @@ hipError_t launch_quantize_rowwise_t(const void *x, int64_t rows, int64_t cols, 
     else if (chunks <= 1024) SB_BLOCK(4);
     else if (chunks <= 1536) SB_BLOCK(6);
     else if (chunks <= 2048) SB_BLOCK(8);
-    else quantize_rowwise_wide_kernel<CODE><<<block_grid, 256, 0, stream>>>(xp, chunks, qp, state);
+    else quantize_rowwise_wide_kernel<CODE><<<block_grid, 256, 0, stream>>>(xp, chunks, qp, state, job);
 #undef SB_WAVE
 #undef SB_BLOCK
     return hipGetLastError();
@@ -455,9 +494,7 @@ hipError_t launch_quantize_tensorwise_t(const void *w, int64_t rows, int64_t col
                                         float *state, unsigned int *partials, hipStream_t stream) {
     const int64_t nchunks = rows * cols / 8;
     const v4u *wp = static_cast<const v4u *>(w);
-    int nblocks = (int)((nchunks + 256 * 4 - 1) / (256 * 4));
-    if (nblocks > kTensorwisePartials) nblocks = kTensorwisePartials;
-    if (nblocks < 1) nblocks = 1;
+    const int nblocks = tensorwise_partial_blocks(nchunks);
     absmax_partial_kernel<<<nblocks, 256, 0, stream>>>(wp, nchunks, partials);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -468,9 +505,47 @@ hipError_t launch_quantize_tensorwise_t(const void *w, int64_t rows, int64_t col
     return hipGetLastError();
 }
 
+// The two quantizers of a forward pass in two launches instead of three: X row-wise with the first pass of W's
+// tensor-wise quantizer riding on the same launch, then W's second pass.  Same results as the separate calls, bit for
+// bit (the partial maxima are formed by the same workgroup bodies over the same chunks).  CODE_X / CODE_W as above.
+template <int CODE_X, int CODE_W>
+hipError_t launch_quantize_forward_operands_t(const void *x, int64_t b, int64_t n, void *xq, float *state_x,
+                                              const void *w, int64_t m, int8_t *wq, int8_t *wq_t, float *state_w,
+                                              unsigned int *partials, hipStream_t stream) {
+    if (b == 0) return launch_quantize_tensorwise_t<CODE_W>(w, m, n, wq, wq_t, state_w, partials, stream);
+    const int64_t nchunks = m * n / 8;
+    const v4u *wp = static_cast<const v4u *>(w);
+    TensorAbsmaxJob job{wp, nchunks, partials, tensorwise_partial_blocks(nchunks), 0};
+    hipError_t e = launch_quantize_rowwise_t<CODE_X>(x, b, n, xq, state_x, stream, job);
+    if (e != hipSuccess) return e;
+    dim3 grid((unsigned int)((n + kTile - 1) / kTile), (unsigned int)((m + kTile - 1) / kTile));
+    quantize_tensorwise_kernel<CODE_W><<<grid, 256, 0, stream>>>(wp, (int)m, (int)n, wq, wq_t, state_w, partials,
+                                                                 job.nblocks);
+    return hipGetLastError();
+}
+
 hipError_t launch_quantize_tensorwise(const void *w, int64_t rows, int64_t cols, int8_t *q, int8_t *q_t,
                                       float *state, unsigned int *partials, hipStream_t stream) {
     return launch_quantize_tensorwise_t<CODE_INT8>(w, rows, cols, q, q_t, state, partials, stream);
+}
+
+hipError_t launch_quantize_forward_operands(const void *x, int64_t b, int64_t n, int8_t *xq, float *state_x,
+                                            const void *w, int64_t m, int8_t *wq, int8_t *wq_t, float *state_w,
+                                            unsigned int *partials, hipStream_t stream) {
+    return launch_quantize_forward_operands_t<CODE_INT8, CODE_INT8>(x, b, n, xq, state_x, w, m, wq, wq_t, state_w,
+                                                                    partials, stream);
+}
+
+hipError_t launch_quantize_forward_operands_f8(const void *x, int64_t b, int64_t n, int fmt_x, uint8_t *xq,
+                                               float *state_x, const void *w, int64_t m, int fmt_w, uint8_t *wq,
+                                               uint8_t *wq_t, float *state_w, unsigned int *partials,
+                                               hipStream_t stream) {
+    int8_t *q = reinterpret_cast<int8_t *>(wq), *q_t = reinterpret_cast<int8_t *>(wq_t);
+#define SB_F8(FX, FW) \
+    launch_quantize_forward_operands_t<FX, FW>(x, b, n, xq, state_x, w, m, q, q_t, state_w, partials, stream)
+    if (fmt_x == 0) return fmt_w == 0 ? SB_F8(CODE_E4M3, CODE_E4M3) : SB_F8(CODE_E4M3, CODE_E5M2);
+    return fmt_w == 0 ? SB_F8(CODE_E5M2, CODE_E4M3) : SB_F8(CODE_E5M2, CODE_E5M2);
+#undef SB_F8
 }
 
 hipError_t launch_quantize_tensorwise_f8(const void *w, int64_t rows, int64_t cols, int fmt, uint8_t *codes,

@@ -39,6 +39,15 @@ hipError_t launch_quantize_colwise_transpose(const void *w, int64_t rows, int64_
                                              void *partials, hipStream_t stream);
 hipError_t launch_quantize_tensorwise(const void *w, int64_t rows, int64_t cols, int8_t *q, int8_t *q_t,
                                       float *state, unsigned int *partials, hipStream_t stream);
+// X row-wise and W [m,n] tensor-wise (both code layouts) in two launches: the first pass of W's quantizer rides on X's
+// launch.  Results are those of the separate launchers, bit for bit.
+hipError_t launch_quantize_forward_operands(const void *x, int64_t b, int64_t n, int8_t *xq, float *state_x,
+                                            const void *w, int64_t m, int8_t *wq, int8_t *wq_t, float *state_w,
+                                            unsigned int *partials, hipStream_t stream);
+hipError_t launch_quantize_forward_operands_f8(const void *x, int64_t b, int64_t n, int fmt_x, uint8_t *xq,
+                                               float *state_x, const void *w, int64_t m, int fmt_w, uint8_t *wq,
+                                               uint8_t *wq_t, float *state_w, unsigned int *partials,
+                                               hipStream_t stream);
 hipError_t launch_quantize_rowwise_f8(const void *x, int64_t rows, int64_t cols, int fmt, uint8_t *codes, float *state,
                                       hipStream_t stream);
 hipError_t launch_quantize_tensorwise_f8(const void *w, int64_t rows, int64_t cols, int fmt, uint8_t *codes,

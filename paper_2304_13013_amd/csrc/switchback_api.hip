@@ -137,12 +137,10 @@ int switchback_forward_bias_layerscale(const void *x_bf16, const void *w_bf16, c
     if (ws_bytes < switchback_workspace_bytes(SB_OP_FORWARD, b, n, m)) return SB_WORKSPACE_TOO_SMALL;
     hipStream_t s = static_cast<hipStream_t>(stream);
     // Algorithm 1's forward pass; the product's epilogue continues with the layer's bias and the block's layer-scale.
-    hipError_t e = sb::launch_quantize_tensorwise(w_bf16, m, n, saved->wq, saved->wq_t, saved->state_w,
-                                                  static_cast<unsigned int *>(ws), s);
+    hipError_t e = sb::launch_quantize_forward_operands(x_bf16, b, n, saved->xq, saved->state_x, w_bf16, m, saved->wq,
+                                                        saved->wq_t, saved->state_w, static_cast<unsigned int *>(ws), s);
     if (e != hipSuccess) return SB_HIP_ERROR;
     if (b == 0) return SB_OK;
-    e = sb::launch_quantize_rowwise(x_bf16, b, n, saved->xq, saved->state_x, s);
-    if (e != hipSuccess) return SB_HIP_ERROR;
     return from_hip(sb::launch_gemm_i8_dequant_post(saved->xq, saved->state_x, saved->wq, saved->state_w, bias, gamma,
                                                     b, m, n, y, y_dtype, s));
 }
@@ -159,14 +157,12 @@ int switchback_forward(const void *x_bf16, const void *w_bf16, int64_t b, int64_
     if (ws == nullptr || !aligned16(ws)) return SB_INVALID_ARG;
     if (ws_bytes < switchback_workspace_bytes(SB_OP_FORWARD, b, n, m)) return SB_WORKSPACE_TOO_SMALL;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    // Algorithm 1, forward: X_int8, state_X = row-wise quantize(X); W_int8, state_W = tensor-wise quantize(W);
-    // Y = int8 matmul fused with the dequantization.
-    hipError_t e = sb::launch_quantize_tensorwise(w_bf16, m, n, saved->wq, saved->wq_t, saved->state_w,
-                                                  static_cast<unsigned int *>(ws), s);
+    // Algorithm 1, forward: X_int8, state_X = row-wise quantize(X); W_int8, state_W = tensor-wise quantize(W) (its
+    // absmax pass rides on the row-wise launch); Y = int8 matmul fused with the dequantization.
+    hipError_t e = sb::launch_quantize_forward_operands(x_bf16, b, n, saved->xq, saved->state_x, w_bf16, m, saved->wq,
+                                                        saved->wq_t, saved->state_w, static_cast<unsigned int *>(ws), s);
     if (e != hipSuccess) return SB_HIP_ERROR;
     if (b == 0) return SB_OK;
-    e = sb::launch_quantize_rowwise(x_bf16, b, n, saved->xq, saved->state_x, s);
-    if (e != hipSuccess) return SB_HIP_ERROR;
     return from_hip(sb::launch_gemm_i8_dequant(saved->xq, saved->state_x, saved->wq, saved->state_w, nullptr, b, m, n, y,
                                                y_dtype, s));
 }
@@ -187,11 +183,10 @@ int switchback_forward_static(const void *x_bf16, const void *w_bf16, int64_t b,
     hipStream_t s = static_cast<hipStream_t>(stream);
     // The kernel sequence of switchback_forward.  Nothing in the scratch has to start at zero: the first pass writes
     // every partial maximum the second pass reads.
-    hipError_t e = sb::launch_quantize_tensorwise(w_bf16, m, n, saved->wq, saved->wq_t, saved->state_w, partials, s);
+    hipError_t e = sb::launch_quantize_forward_operands(x_bf16, b, n, saved->xq, saved->state_x, w_bf16, m, saved->wq,
+                                                        saved->wq_t, saved->state_w, partials, s);
     if (e != hipSuccess) return SB_HIP_ERROR;
     if (b == 0) return SB_OK;
-    e = sb::launch_quantize_rowwise(x_bf16, b, n, saved->xq, saved->state_x, s);
-    if (e != hipSuccess) return SB_HIP_ERROR;
     return from_hip(sb::launch_gemm_i8_dequant(saved->xq, saved->state_x, saved->wq, saved->state_w, nullptr, b, m, n, y,
                                                y_dtype, s));
 }
@@ -367,12 +362,11 @@ int switchback_forward_f8(const void *x_bf16, const void *w_bf16, int64_t b, int
     hipStream_t s = static_cast<hipStream_t>(stream);
     uint8_t *xq = reinterpret_cast<uint8_t *>(saved->xq), *wq = reinterpret_cast<uint8_t *>(saved->wq);
     // The forward pass of Algorithm 1 with float8cast(x / absmax) as the quantizer.
-    hipError_t e = sb::launch_quantize_tensorwise_f8(w_bf16, m, n, fmt_w, wq, reinterpret_cast<uint8_t *>(saved->wq_t),
-                                                     saved->state_w, static_cast<unsigned int *>(ws), s);
+    hipError_t e = sb::launch_quantize_forward_operands_f8(x_bf16, b, n, fmt_x, xq, saved->state_x, w_bf16, m, fmt_w, wq,
+                                                           reinterpret_cast<uint8_t *>(saved->wq_t), saved->state_w,
+                                                           static_cast<unsigned int *>(ws), s);
     if (e != hipSuccess) return SB_HIP_ERROR;
     if (b == 0) return SB_OK;
-    e = sb::launch_quantize_rowwise_f8(x_bf16, b, n, fmt_x, xq, saved->state_x, s);
-    if (e != hipSuccess) return SB_HIP_ERROR;
     return from_hip(sb::launch_gemm_f8_dequant(xq, fmt_x, saved->state_x, wq, fmt_w, saved->state_w, b, m, n, y,
                                                y_dtype, s));
 }
