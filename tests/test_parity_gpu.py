@@ -919,6 +919,41 @@ def test_float8_layer_is_deterministic_and_rejects_unsupported_widths():
 
 
 # ---------------------------------------------------------------------------------------------------------------
+# seeded random shapes: ragged M, every multiple-of-64 width class, all kernel instances (which one runs depends on
+# K % 128 and on the tile count), every output mode, whole outputs
+# ---------------------------------------------------------------------------------------------------------------
+
+def random_shapes(seed, count, max_m, max_n, max_k):
+    rng = np.random.default_rng(seed)
+    return [(int(rng.integers(1, max_m + 1)), 64 * int(rng.integers(1, max_n // 64 + 1)),
+             64 * int(rng.integers(1, max_k // 64 + 1))) for _ in range(count)]
+
+
+@pytest.mark.parametrize("M,N,K", random_shapes(101, 16, 2500, 1536, 1024) + random_shapes(102, 6, 12000, 6144, 384))
+def test_int8_product_random_shapes(oracle, M, N, K):
+    rng = np.random.default_rng(M * 7 + N * 3 + K)
+    a = rng.integers(-127, 128, size=(M, K)).astype(np.int8)
+    b = rng.integers(-127, 128, size=(N, K)).astype(np.int8)
+    srow = (rng.random(M) * 2 + 0.25).astype(np.float32)
+    check_int8_product_whole(oracle, a, b, srow, 0.4375)
+    bias, gamma = rng.standard_normal(N).astype(np.float32), rng.standard_normal(N).astype(np.float32)
+    dev = lambda v: torch.from_numpy(v).to(DEV)
+    args = (dev(a), dev(srow), dev(b), torch.tensor([0.4375], device=DEV), dev(bias), dev(gamma))
+    o32 = host(sb.matmul_int8_dequant_bias_layerscale(*args, out_dtype=torch.float32))
+    obf = bits_of(sb.matmul_int8_dequant_bias_layerscale(*args, out_dtype=torch.bfloat16))
+    assert_bias_layerscale(o32, obf, oracle.matmul_int8(a, b), srow, 0.4375, bias, gamma, oracle)
+
+
+@pytest.mark.parametrize("b,n,m", [(mm, nn, kk) for (mm, nn, kk) in random_shapes(103, 10, 5000, 1024, 1024)])
+def test_weight_gradient_random_shapes(oracle, b, n, m):
+    rng = np.random.default_rng(b + 5 * n + 11 * m)
+    dyb, xb = rand_bf16(rng, (b, m), 0.1), rand_bf16(rng, (b, n))
+    dw32 = host(sb.backward_weight(to_dev(dyb), to_dev(xb), dw_dtype=torch.float32))
+    dw_ref = oracle.weight_grad(dyb, xb)
+    assert np.abs(dw32.astype(np.float64) - dw_ref).max() <= 1e-2 * float(np.sqrt((dw_ref ** 2).mean()))
+
+
+# ---------------------------------------------------------------------------------------------------------------
 # maximum sizes: operands that end just below the 4 GiB reach of the kernels' 32-bit buffer offsets
 # ---------------------------------------------------------------------------------------------------------------
 
