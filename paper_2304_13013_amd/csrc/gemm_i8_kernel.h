@@ -10,7 +10,8 @@
 //   * 256x256 output tile per workgroup of eight waves, two per SIMD; a wave tile is 64 columns wide and 128 rows
 //     high (96 and 160 with the uneven split below).  A persistent grid (one workgroup per compute unit) walks the
 //     tiles in an order that keeps the workgroups of one XCD (workgroup id % 8) on a compact patch of tiles, so its
-//     L2 sees each operand panel once.
+//     L2 sees each operand panel once.  The tile and the wave grid are parameters of GemmI8Cfg; the other instance in
+//     use is 128x128 with four waves, two workgroups per compute unit, for products with few tiles.
 //   * Operand tiles go HBM/L2 -> LDS with buffer_load_dwordx4 ... lds (no VGPR staging), STAGES deep.  One wave
 //     instruction fills 1 KiB of LDS linearly, so the bank-conflict-avoiding swizzle is applied on the GLOBAL side:
 //     LDS slot (row, p) holds 16-byte k-chunk p ^ f(row) of that row, f(row) = (row / (256/BK)) % (BK/16).  Rows past
