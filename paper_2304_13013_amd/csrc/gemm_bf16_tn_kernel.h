@@ -11,7 +11,8 @@
 //
 // Pipeline, wave roles and barriers are those of the int8 kernel (gemm_i8_kernel.h): 256x256 tile, 8 waves with
 // 128x64 wave tiles, two LDS stages of 64 tokens, four loader waves, fragment reads issued between the MFMAs of
-// the preceding k-step, bare s_barrier with counted waits.
+// the preceding k-step, bare s_barrier with counted waits.  A second instance has 128x128 tiles and four waves with
+// 64x64 wave tiles, two workgroups per compute unit.
 // The X-side tile is the MFMA's first operand and the dY-side tile its second, so a lane owns one dW row.
 //
 // The contraction is long (b ~ 32k) and the output small, so work items are (split, tile) pairs (split-K); they are
@@ -34,24 +35,35 @@ struct GemmBf16Args {
     int out_bf16;
 };
 
-template <int STAGES_ = 2, int LOADERS_ = 4, int MT_LOADER_ = 4, int BKT_ = 64>
+// TILE_ x TILE_ output tile per workgroup of WAVES_M_ x WAVES_N_ waves (wave tile TILE_/WAVES_M_ rows by 64 columns).
+// The default is the 256 x 256 tile of eight waves, one workgroup per compute unit.  The 128 x 128 tile of four waves
+// takes 80 KiB of LDS, so two workgroups share a compute unit; it moves twice the operand bytes per multiply-add and
+// serves weight gradients with too few large tiles to fill the GPU without many splits.
+template <int STAGES_ = 2, int LOADERS_ = 4, int MT_LOADER_ = 4, int BKT_ = 64, int TILE_ = 256, int WAVES_M_ = 2,
+          int WAVES_N_ = 4>
 struct GemmBf16Cfg {
-    static constexpr int MT_LOADER = MT_LOADER_;  // 32-row MFMA blocks of a loader wave's tile; when < 4 its SIMD partner
-                                                  // (wave + 4) takes the other 8 - MT_LOADER blocks of the wave column
-    static constexpr int BM = 256, BN = 256, BKT = BKT_;  // dW rows (dY columns), dW columns (X columns), tokens/stage
-    static constexpr int REQ_OP = BKT / 2;                    // 1 KiB requests (two token rows) per operand tile
+    static constexpr int BM = TILE_, BN = TILE_, BKT = BKT_;  // dW rows (dY columns), dW columns (X columns), tokens/stage
+    static constexpr int PITCH = TILE_ * 2;                   // bytes of one token row of an operand tile in LDS
+    static constexpr int CHUNKS = PITCH / 16;                 // 16-byte column chunks per token row
+    static constexpr int ROWS_PER_REQ = 1024 / PITCH;         // token rows one 1 KiB request fills
+    static constexpr int NVOFF = 4 / ROWS_PER_REQ;            // distinct (token % 4) swizzles among a wave's requests
+    static constexpr int REQ_OP = BKT / ROWS_PER_REQ;         // 1 KiB requests per operand tile
     static constexpr int STAGES = STAGES_, LOADERS = LOADERS_;
-    static constexpr int WAVES_M = 2, WAVES_N = 4, NWAVES = 8, THREADS = 512;
-    static constexpr int WTM = 128, WTN = 64, NT = 2;
+    static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, NWAVES = WAVES_M * WAVES_N, THREADS = NWAVES * 64;
+    static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N, NT = WTN / 32;
+    static constexpr int MT_EVEN = WTM / 32;                  // 32-row MFMA blocks per wave tile when all waves get the same
+    static constexpr int MT_LOADER = MT_LOADER_;  // 32-row MFMA blocks of a loader wave's tile; when < MT_EVEN its SIMD partner
+                                                  // (wave + 4) takes the other 2 * MT_EVEN - MT_LOADER blocks of the wave column
     static constexpr int KK = BKT / 16;                       // MFMA k-steps (16 tokens) per stage
-    static constexpr int OP_BYTES = BKT * 512;                // one operand tile: BKT token rows of 256 bf16
+    static constexpr int OP_BYTES = BKT * PITCH;              // one operand tile: BKT token rows
     static constexpr int STAGE_BYTES = 2 * OP_BYTES;          // dY tile then X tile
-    static constexpr int LPW = STAGE_BYTES / 1024 / LOADERS;  // 1 KiB requests (two token rows of one operand) per loader wave
+    static constexpr int LPW = STAGE_BYTES / 1024 / LOADERS;  // 1 KiB requests (of one operand) per loader wave
     static constexpr int EPI_WAVE_BYTES = 32 * WTN * 2, EPI_PIECES = WTN * 2 / 16;
     static constexpr int LDS_BYTES = STAGES * STAGE_BYTES + NWAVES * EPI_WAVE_BYTES;
-    static_assert(STAGES >= 2 && LDS_BYTES <= 160 * 1024 && (LOADERS == 4 || LOADERS == 8), "configuration");
-    static_assert(MT_LOADER == 4 || (LOADERS == 4 && MT_LOADER == 3), "uneven split");
-    static_assert((BKT == 64 || BKT == 32) && LPW % 2 == 0 && REQ_OP % LPW == 0, "stage length");
+    static_assert(STAGES >= 2 && LDS_BYTES <= 160 * 1024 && (LOADERS == 4 || LOADERS == 8) && LOADERS <= NWAVES, "configuration");
+    static_assert((TILE_ == 256 || TILE_ == 128) && NT == 2 && MT_EVEN >= 2 && MT_EVEN <= 4, "tile");
+    static_assert(MT_LOADER == MT_EVEN || (LOADERS == 4 && NWAVES == 8 && WAVES_M == 2 && MT_LOADER == 3), "uneven split");
+    static_assert((BKT == 64 || BKT == 32) && LPW % NVOFF == 0 && REQ_OP % LPW == 0, "stage length");
     static_assert(LPW * (STAGES - 1) < 64, "vmcnt range");
 };
 
@@ -68,11 +80,13 @@ __device__ __forceinline__ void gemm_bf16_tn_role(const GemmBf16Args &p, const i
     const int frow = lane & 31, fhalf = lane >> 5;
 
     // Loader role (see the int8 kernel for why only LOADERS waves issue requests, all right after a hand-over).
-    // Request i of loader wave w fills 1 KiB = token rows (2j, 2j+1) of one operand tile, j = (w*LPW + i) % REQ_OP; the
-    // first 32 requests of a stage load dY, the rest X, so a wave loads one operand only.  LDS slot (token, p) holds
-    // 16-byte column chunk p ^ ((token & 3) << 2): token rows are 512 bytes apart, so without it the four token rows
-    // one transposing read touches would all fall into the same 64-byte bank window.  A lane's byte offset is
-    //   voff[i & 1] (per lane: its token of the pair, its swizzled chunk) + i * 4 * ld + item_soff + kt * BKT * 2 * ld.
+    // Request i of loader wave w fills 1 KiB = ROWS_PER_REQ consecutive token rows of one operand tile, the
+    // ((w*LPW + i) % REQ_OP)-th such group; the first REQ_OP requests of a stage load dY, the rest X, so a wave loads
+    // one operand only.  LDS slot (token, p) holds 16-byte column chunk p ^ ((token & 3) << 2): token rows are a
+    // multiple of 256 bytes apart, so without it the four token rows one transposing read touches would all fall into
+    // the same 64-byte bank window.  A lane's byte offset is
+    //   voff[i % NVOFF] (per lane: its token row of the group, its swizzled chunk) + i * req_step + item_soff
+    //   + kt * stage_step.
     // Columns past the operand's width (partial tiles) read the next token row or, at the very end, zeros from the
     // bounds check; they only feed results that are never stored.
     const bool loader = wave < C::LOADERS;
@@ -81,12 +95,13 @@ __device__ __forceinline__ void gemm_bf16_tn_role(const GemmBf16Args &p, const i
     // The bounds check of the buffer resource (num_records in bytes) turns token rows past b into zeros.
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
         (void *)(loads_dy ? p.dy : p.x), 0, (unsigned)((size_t)p.b * ld * 2), 0x00020000);
-    const int l_tok = lane >> 5, l_pos = lane & 31;
-    const int tok0 = ((wave * C::LPW) % C::REQ_OP) * 2;  // first token row of the wave's share within a stage
-    unsigned voff[2];
+    const int l_tok = lane / C::CHUNKS, l_pos = lane % C::CHUNKS;  // token row of the request, 16-byte chunk of it
+    const int tok0 = ((wave * C::LPW) % C::REQ_OP) * C::ROWS_PER_REQ;  // first token row of the wave's share within a stage
+    unsigned voff[C::NVOFF];
 #pragma unroll
-    for (int v = 0; v < 2; ++v) voff[v] = ((unsigned)l_tok * ld + ((l_pos ^ ((2 * v + l_tok) << 2)) << 3)) * 2;
-    const unsigned req_step = 4 * ld, stage_step = (unsigned)C::BKT * 2 * ld;
+    for (int v = 0; v < C::NVOFF; ++v)
+        voff[v] = ((unsigned)l_tok * ld + ((l_pos ^ (((C::ROWS_PER_REQ * v + l_tok) & 3) << 2)) << 3)) * 2;
+    const unsigned req_step = (unsigned)C::ROWS_PER_REQ * 2 * ld, stage_step = (unsigned)C::BKT * 2 * ld;
     unsigned item_soff = 0;
     auto set_item_sources = [&](int tm, int tn, int k_begin) {
         item_soff = ((unsigned)(k_begin + tok0) * ld + (unsigned)(loads_dy ? tm * C::BM : tn * C::BN)) * 2;
@@ -96,7 +111,7 @@ __device__ __forceinline__ void gemm_bf16_tn_role(const GemmBf16Args &p, const i
         const unsigned soff = item_soff + (unsigned)kt * stage_step;
 #pragma unroll
         for (int i = 0; i < C::LPW; ++i)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)(dst + i * 1024), 16, voff[i & 1],
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)(dst + i * 1024), 16, voff[i % C::NVOFF],
                                                      soff + (unsigned)i * req_step, 0, 0);
     };
 
@@ -109,9 +124,9 @@ __device__ __forceinline__ void gemm_bf16_tn_role(const GemmBf16Args &p, const i
     // The k-step, the second read (+4 tokens) and the stage only add constants: tok = kk*16 + half*4 + f_tok keeps
     // tok & 3 == f_tok & 3, so the swizzle term is fixed per lane.
     auto frag_off = [&](int op_base, int col0) -> int {
-        const int col = col0 + f_col;  // column within the 256-column operand tile
+        const int col = col0 + f_col;  // column within the operand tile
         const int chunk = (col >> 3) ^ ((f_tok & 3) << 2);
-        return op_base + f_tok * 512 + chunk * 16 + (col & 7) * 2;
+        return op_base + f_tok * C::PITCH + chunk * 16 + (col & 7) * 2;
     };
     int goff[MT], xoff[C::NT];
 #pragma unroll
@@ -125,7 +140,7 @@ __device__ __forceinline__ void gemm_bf16_tn_role(const GemmBf16Args &p, const i
     auto read_pair = [&](unsigned addr) -> v8bf {
         v2u lo, hi;
         asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo) : "v"(addr));
-        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:2048" : "=v"(hi) : "v"(addr));
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(addr), "n"(4 * C::PITCH));
         return __builtin_bit_cast(v8bf, __builtin_shufflevector(lo, hi, 0, 1, 2, 3));
     };
     // Fragment schedule of the int8 kernel: a k-step group issues its MFMAs in the order (g0,x0) (g0,x1) (g1,x0) ...
@@ -134,7 +149,7 @@ __device__ __forceinline__ void gemm_bf16_tn_role(const GemmBf16Args &p, const i
     static_assert(C::NT == 2, "fragment schedule below is written for MT x 2 MFMA blocks per wave");
     constexpr int NFRAG = MT + C::NT;
     auto issue_frag_read = [&](int i, int buf, int kt, int kk) {
-        const unsigned base = lds_base + (kt % S) * C::STAGE_BYTES + kk * (16 * 512);
+        const unsigned base = lds_base + (kt % S) * C::STAGE_BYTES + kk * (16 * C::PITCH);
         switch (i) {
             case 0: xf[buf][0] = read_pair(base + xoff[0]); break;
             case 1: gf[buf][0] = read_pair(base + goff[0]); break;
@@ -348,12 +363,12 @@ __device__ __forceinline__ void gemm_bf16_tn_role(const GemmBf16Args &p, const i
 template <class C>
 __device__ __forceinline__ void gemm_bf16_tn_body(const GemmBf16Args &p) {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform: what derives from it is scalar
-    if (C::MT_LOADER == 4)
-        gemm_bf16_tn_role<C, 4>(p, wave, (wave / C::WAVES_N) * C::WTM);
+    if (C::MT_LOADER == C::MT_EVEN)
+        gemm_bf16_tn_role<C, C::MT_EVEN>(p, wave, (wave / C::WAVES_N) * C::WTM);
     else if (wave < C::LOADERS)
         gemm_bf16_tn_role<C, C::MT_LOADER>(p, wave, 0);
     else
-        gemm_bf16_tn_role<C, 8 - C::MT_LOADER>(p, wave, C::MT_LOADER * 32);
+        gemm_bf16_tn_role<C, 2 * C::MT_EVEN - C::MT_LOADER>(p, wave, C::MT_LOADER * 32);
 }
 
 }  // namespace sb

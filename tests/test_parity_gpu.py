@@ -578,8 +578,9 @@ def test_layer_vit_h14_whole_output(oracle, layer):
 
 @pytest.mark.parametrize("b,n,m", [(256, 4352, 4352), (1500, 2304, 2816), (4000, 1280, 1280)])
 def test_weight_gradient_whole_output_over_several_rounds(oracle, b, n, m):
-    """More work items than workgroups (289 tiles; 99 tiles without and 25 tiles with a split of the token range), so
-    every workgroup of the persistent grid takes a second item: dW compared with the oracle on every element."""
+    """More work items than workgroups, so workgroups of the persistent grid take a second item: 289 large tiles
+    without a split of the token range; 198 and 100 small tiles (the instance for short work items) with one.  dW
+    compared with the oracle on every element."""
     rng = np.random.default_rng(b + n + m)
     dyb, xb = rand_bf16(rng, (b, m), 0.1), rand_bf16(rng, (b, n))
     dy, x = to_dev(dyb), to_dev(xb)
@@ -587,6 +588,22 @@ def test_weight_gradient_whole_output_over_several_rounds(oracle, b, n, m):
     dwbf = bits_of(sb.backward_weight(dy, x, dw_dtype=torch.bfloat16))
     dw_ref = oracle.weight_grad(dyb, xb)
     assert np.abs(dw32.astype(np.float64) - dw_ref).max() <= 1e-2 * float(np.sqrt((dw_ref ** 2).mean()))
+    np.testing.assert_array_equal(dwbf, oracle.round_to_bf16(dw32))
+
+
+def test_weight_gradient_large_tiles_with_splits(oracle):
+    """Long token range, few tiles: the 256 x 256-tile instance with the token range cut into four pieces (64 tiles x 4
+    splits, ragged last stage and ragged last tile row / column).  Every seventh row of dW (all residues modulo the
+    32-row matrix-instruction block, every tile) compared on all columns."""
+    b, n, m = 8600 + 37, 2048 - 128, 2048 - 64
+    rng = np.random.default_rng(77)
+    dyb, xb = rand_bf16(rng, (b, m), 0.1), rand_bf16(rng, (b, n))
+    dy, x = to_dev(dyb), to_dev(xb)
+    dw32 = host(sb.backward_weight(dy, x, dw_dtype=torch.float32))
+    dwbf = bits_of(sb.backward_weight(dy, x, dw_dtype=torch.bfloat16))
+    rows = np.arange(0, m, 7)
+    dw_ref = oracle.weight_grad(np.ascontiguousarray(dyb[:, rows]), xb)
+    assert np.abs(dw32[rows].astype(np.float64) - dw_ref).max() <= 1e-2 * float(np.sqrt((dw_ref ** 2).mean()))
     np.testing.assert_array_equal(dwbf, oracle.round_to_bf16(dw32))
 
 
