@@ -27,8 +27,8 @@ PEAK = {"hbm_GBps": 8000.0, "int8_TOPs": 5000.0, "bf16_TFLOPs": 2500.0}
 # time: the table belongs to the kernels as they were when that profile was taken (tile walk, grid and split choices
 # decide the figures), and is null for other workloads.
 TRAFFIC_BYTES_PER_LAUNCH_VIT_H14 = {
-    "gemm_int8_dequant": 318.3e6 + 169.6e6,        # 8 launches per step; algorithmic mean 257.6e6
-    "gemm_bf16_weight_grad": 581.6e6 + 97.9e6,     # 4 launches per step, fp32 split-K partials included; the reduction
+    "gemm_int8_dequant": 318.4e6 + 168.8e6,        # 8 launches per step; algorithmic mean 257.6e6
+    "gemm_bf16_weight_grad": 583.7e6 + 97.9e6,     # 4 launches per step, fp32 split-K partials included; the reduction
                                                    # kernel of the same step adds 96.7e6 + 9.8e6; algorithmic 346.7e6
     "quantize_rowwise": 258.2e6,                   # 8 launches per step, 4 of them with the absmax pass of W riding
 }
