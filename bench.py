@@ -37,7 +37,7 @@ TRAFFIC_BYTES_PER_LAUNCH_VIT_H14 = {
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="vit_h14", help="workload (default: the headline ViT-H/14 shapes)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
