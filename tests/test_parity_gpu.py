@@ -545,12 +545,19 @@ def test_int8_product_whole_output_over_several_rounds(oracle, M, N, K):
     check_int8_product_whole(oracle, a, b, srow, 0.21875)
 
 
-@pytest.mark.parametrize("layer", [1, 3])
-def test_layer_vit_h14_whole_output(oracle, layer):
-    """ViT-H/14 proj (1280 -> 1280) and fc2 (5120 -> 1280) in the launch configuration the benchmark times: Y and dX
-    compared with the oracle on every element (raw accumulators, binary32, bf16); for proj also the whole dW."""
-    L = I.CONFIGS["vit_h14"].layers[layer]
-    d = I.make_layer_inputs("vit_h14", layer)
+WHOLE = [("vit_h14", 1, True), ("vit_h14", 3, False), ("vit_l14", 1, True),
+         ("vit_b16", 0, True), ("vit_b16", 1, True)]
+
+
+@pytest.mark.parametrize("config,layer,with_dw", WHOLE, ids=["%s-%d" % (c, l) for c, l, _ in WHOLE])
+def test_layer_whole_output(oracle, config, layer, with_dw):
+    """Layers in the launch configuration the benchmark times, compared with the oracle on every element: Y and dX
+    (raw accumulators, binary32, bf16) and, except for the largest, the whole dW.  ViT-H/14 proj (1280 -> 1280) and fc2
+    (5120 -> 1280) run the 256 x 256-tile instances over several rounds of the persistent grids; ViT-L/14 proj and both
+    layers of ViT-B/16 run the weight gradient, and ViT-B/16's 768-wide outputs also the int8 products, on the 128 x 128-tile
+    instances."""
+    L = I.CONFIGS[config].layers[layer]
+    d = I.make_layer_inputs(config, layer)
     xq, sx = oracle.quantize_rowwise(d["x"])
     wq, wq_t, sw = oracle.quantize_tensorwise(d["w"])
     gq, sg = oracle.quantize_rowwise(d["dy"])
@@ -566,14 +573,16 @@ def test_layer_vit_h14_whole_output(oracle, layer):
     assert_bf16_is_rounding_within_one_ulp(ybf, ref, oracle)
     ref = oracle.dequantize(oracle.matmul_int8(gq, wq_t), sg, sw)
     assert_bf16_is_rounding_within_one_ulp(dxbf, ref, oracle)
-    del ref, ybf, dxbf, bufs
+    del ref, ybf, dxbf
     # the same two products through the product call: raw accumulators and binary32 as well
     check_int8_product_whole(oracle, xq, wq, sx, sw)
     check_int8_product_whole(oracle, gq, wq_t, sg, sw)
-    if layer == 1:
-        dw32 = host(sb.backward_weight(dy, x, dw_dtype=torch.float32)).astype(np.float64)
+    if with_dw:
+        dw32 = host(sb.backward_weight(dy, x, bufs, dw_dtype=torch.float32))
+        dwbf = bits_of(sb.backward_weight(dy, x, bufs, dw_dtype=torch.bfloat16))
         dw_ref = oracle.weight_grad(d["dy"], d["x"])
-        assert np.abs(dw32 - dw_ref).max() <= 1e-2 * float(np.sqrt((dw_ref ** 2).mean()))
+        assert np.abs(dw32.astype(np.float64) - dw_ref).max() <= 1e-2 * float(np.sqrt((dw_ref ** 2).mean()))
+        np.testing.assert_array_equal(dwbf, oracle.round_to_bf16(dw32))
 
 
 @pytest.mark.parametrize("b,n,m", [(256, 4352, 4352), (1500, 2304, 2816), (4000, 1280, 1280)])
