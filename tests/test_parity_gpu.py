@@ -1031,9 +1031,12 @@ def test_weight_gradient_at_the_largest_operand(oracle):
 # is repeated many times on the benchmark's shapes and every result must equal the first bit for bit
 # ---------------------------------------------------------------------------------------------------------------
 
-@pytest.mark.parametrize("layer", [1, 2, 3])
-def test_products_are_repeatable_at_full_size(layer):
-    L = I.CONFIGS["vit_h14"].layers[layer]
+@pytest.mark.parametrize("config,layer", [("vit_h14", 1), ("vit_h14", 2), ("vit_h14", 3), ("vit_l14", 1),
+                                          ("vit_b16", 0), ("vit_b16", 1)])
+def test_products_are_repeatable_at_full_size(config, layer):
+    """ViT-H/14: the 256 x 256-tile instances; ViT-L/14 proj and ViT-B/16: the 128 x 128-tile instances of the weight
+    gradient (and, for ViT-B/16's 768-wide outputs, of the 8-bit products)."""
+    L = I.CONFIGS[config].layers[layer]
     g = torch.Generator(device=DEV)
     g.manual_seed(50 + layer)
     x = torch.randn((L.b, L.n), generator=g, device=DEV).to(torch.bfloat16)
